@@ -1,0 +1,195 @@
+/*
+ * libpoly -- MI355X (gfx950) hot path of Polymorph: per-frame context selection and the
+ * forward of a shared ViT backbone whose frames each run their own unmerged LoRA adapters.
+ *
+ * Conventions
+ *   - Plain C ABI.  Every tensor pointer is a DEVICE pointer unless it says "host".
+ *     The structs themselves (poly_model_desc, poly_base_weights, ...) live in host memory.
+ *   - The caller owns every buffer.  The library allocates nothing and keeps no state
+ *     between calls; scratch memory comes in through `workspace`.
+ *   - Every call is asynchronous on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  Outputs are valid once the stream has been synchronised.
+ *   - Return value: POLY_OK or a negative poly_status.  Conditions that only the device can
+ *     see (an adapter id out of range, offsets that are not monotone) are written to the
+ *     `dev_status` word by the first kernel; the affected call then computes nothing.
+ *   - Matrices are stored with the contraction index fastest.  In the paper's notation a
+ *     linear is y = x W + b with W in R^{D_in x D_out} and an adapter is A in R^{D_in x r},
+ *     B in R^{r x D_out} (Sec. 3.1); this library takes their column-major images
+ *         W -> Wt[D_out][D_in],   A -> At[r][D_in],   B -> Bt[D_out][r].
+ *     "elt" below is float for POLY_F32 and bf16 (uint16 bit pattern) for POLY_BF16; vectors
+ *     (biases, LayerNorm gains and shifts, cls, pos) are always float.
+ *   - Row-block b = (frame f, adapter k): frame f's adapters are
+ *     adapter_ids[row_offsets[f] .. row_offsets[f+1]) -- the CSR image of the active context
+ *     sets S_t of Sec. 3.3; adapter id = context id.
+ */
+#ifndef POLY_H
+#define POLY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum poly_status {
+    POLY_OK = 0,
+    POLY_EINVAL = -1, /* null pointer, bad shape, unsupported size or enum */
+    POLY_ERANGE = -2, /* adapter id outside [0, n_adapters), offsets not monotone, R above its bound */
+    POLY_ECAP = -3,   /* an output or the workspace is too small */
+    POLY_EHIP = -4    /* the HIP runtime reported an error */
+} poly_status;
+
+enum { POLY_F32 = 0, POLY_BF16 = 1 };
+enum { POLY_TGT_QKV = 1, POLY_TGT_PROJ = 2, POLY_TGT_FC1 = 4, POLY_TGT_FC2 = 8 };
+
+/* Limits of this build. */
+enum {
+    POLY_MAX_CONTEXTS = 64,  /* M: one 64-bit set per frame */
+    POLY_MAX_LABELS = 1024,  /* K */
+    POLY_MAX_RANK = 64,      /* r */
+    POLY_MAX_HEAD_CLASSES = 64,
+    POLY_HEAD_DIM = 64       /* D / heads must be 64 */
+};
+
+const char *poly_status_string(int status);
+
+/* ------------------------------------------------------------------------------------------
+ * poly_select -- context detection for a batch of consecutive frames of one stream
+ * (Alg. 2 "Greedy Context Detection with Conditional Context Copy", Sec. 3.5; the cover
+ * constraint is Eq. 2).
+ *
+ *   Y_t = { l : label_scores[t][l] >= theta }                     (the monitor of Sec. 3.2)
+ *   Y_t == Y_{t-1}                                    -> S_t = S_{t-1}
+ *   context_copy and S_{t-1} provides every l in Y_t  -> S_t = S_{t-1}
+ *   else scan the contexts by (size ascending, id ascending) and take a context iff it provides a
+ *   label that is still uncovered, until none is left.
+ * Context C provides label l iff group_membership[C][l] != 0 and (acc == NULL or acc[C][l] >= tau).
+ *
+ *   label_scores      [F][K] float.
+ *   group_membership  [M][K] uint8, 1 iff label l is in context C_m.  M <= 64, K <= 1024.
+ *   opts              host struct below.
+ *   state             device buffer of poly_select_state_bytes(K) bytes carrying (Y_{t-1}, S_{t-1})
+ *                     between calls; all-zero = "no previous frame"; NULL = stateless call.
+ *                     Read and updated by the call.
+ *   row_offsets       [F+1] int32 out.
+ *   adapter_ids       [cap] int32 out, selection order inside a frame.  Ids past `cap` are dropped.
+ *   counters          [2] int32 out: counters[0] = R = total number of (frame, context) rows needed
+ *                     (compare with cap: R > cap means adapter_ids is truncated), counters[1] =
+ *                     number of (frame, label) pairs of Y_t that no context of S_t provides.
+ * Frames are independent unless a state is given or context_copy is set; then a short sequential
+ * pass resolves the reuse branches.  Errors: POLY_EINVAL for null/size violations, POLY_EHIP.
+ */
+typedef struct poly_select_opts {
+    float theta;          /* label threshold, >= is active (0.5) */
+    int32_t context_copy; /* 0 = the paper's main variant */
+    const float *acc;     /* device [M][K] accuracy table a_{C,l}, or NULL */
+    float tau;            /* minimum accuracy, used only with acc */
+} poly_select_opts;
+
+size_t poly_select_state_bytes(int K);
+
+int poly_select(const float *label_scores, int F, int K, const uint8_t *group_membership, int M,
+                const poly_select_opts *opts, void *state, int32_t *row_offsets, int32_t *adapter_ids,
+                int cap, int32_t *counters, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * poly_forward -- forward of F frames through the shared backbone, each (frame, adapter)
+ * row-block as its own branch (Sec. 3.1, Fig. 2; inference path of Fig. 3b):
+ *   tokens: patch embedding of the NHWC frame (patch vector index (i*patch + j)*3 + c) + class
+ *   token + position table; layers [0, L0) once per frame, without adapters; layers [L0, L) per
+ *   row-block with adapter k alone,
+ *       linear_k(x) = x W + b + lora_scale * (x A_k) B_k      on the linears named in `targets`,
+ *   inside the usual pre-LayerNorm block (softmax attention with 64-wide heads, exact-erf GELU
+ *   MLP, residuals); then LayerNorm of the class token and adapter k's own head:
+ *       logits[b] = LN(x_b[0]) H_k + hb_k,   scores[b] = sigmoid(logits[b]).
+ *   W + A_k B_k is never formed.
+ *
+ *   frames        [F][H][W][3] elt.
+ *   row_offsets   [F+1] int32, adapter_ids [>= row_offsets[F]] int32 (device).
+ *   R             host upper bound of row_offsets[F]; the kernels read the true value on the device,
+ *                 so the output of poly_select can be consumed without a host round trip.
+ *   out_logits    [R][C] float, nullable.   out_scores [R][C] float.
+ *   out_merged    [F][K] float, nullable (needs heads->class_map): score of class
+ *                 class_map[k][c] from row-block (f,k), maximum where adapters overlap, 0 where no
+ *                 active adapter reports the class.
+ *   dev_status    device int32, nullable: POLY_OK or POLY_ERANGE after the call.
+ *   workspace     >= poly_forward_workspace_bytes(m, F, R) bytes, 256-byte aligned.
+ * Rows past row_offsets[F] are left untouched.  Results do not depend on where a frame sits in
+ * the batch (fixed reduction order, no atomics on floating-point sums).
+ */
+typedef struct poly_model_desc {
+    int32_t H, W, patch;  /* frame size and patch edge; H, W multiples of patch */
+    int32_t D, heads;     /* model width; D == 64 * heads */
+    int32_t L, Dm;        /* layers, MLP width */
+    int32_t L0;           /* first adapted layer, 0 <= L0 <= L (L - L0 = final 20 % in the paper) */
+    int32_t targets;      /* POLY_TGT_* mask of adapted linears */
+    int32_t r;            /* LoRA rank */
+    int32_t n_adapters;   /* N_ad */
+    int32_t C;            /* classes per adapter head */
+    int32_t dtype;        /* POLY_F32 or POLY_BF16 */
+    float lora_scale;     /* s */
+    float ln_eps;
+} poly_model_desc;
+
+typedef struct poly_base_weights {
+    const void *patch_w;  /* elt [D][3*patch*patch] */
+    const float *patch_b; /* [D] */
+    const float *cls;     /* [D] */
+    const float *pos;     /* [T][D], T = 1 + (H/patch)*(W/patch) */
+    /* stacked over the L layers: */
+    const float *ln1_g, *ln1_b; /* [L][D] */
+    const void *qkv_w;          /* elt [L][3D][D]; output columns ordered q | k | v */
+    const float *qkv_b;         /* [L][3D] */
+    const void *proj_w;         /* elt [L][D][D] */
+    const float *proj_b;        /* [L][D] */
+    const float *ln2_g, *ln2_b; /* [L][D] */
+    const void *fc1_w;          /* elt [L][Dm][D] */
+    const float *fc1_b;         /* [L][Dm] */
+    const void *fc2_w;          /* elt [L][D][Dm] */
+    const float *fc2_b;         /* [L][D] */
+    const float *lnf_g, *lnf_b; /* [D] */
+} poly_base_weights;
+
+typedef struct poly_lora_weights {
+    /* index 0 qkv, 1 proj, 2 fc1, 3 fc2; NULL for linears not in `targets` */
+    const void *At[4]; /* elt [L-L0][N_ad][r][D_in] */
+    const void *Bt[4]; /* elt [L-L0][N_ad][D_out][r] */
+} poly_lora_weights;
+
+typedef struct poly_heads {
+    const void *head_w;       /* elt [N_ad][C][D] */
+    const float *head_b;      /* [N_ad][C] */
+    const int32_t *class_map; /* [N_ad][C] -> label index in [0, K), nullable */
+} poly_heads;
+
+size_t poly_forward_workspace_bytes(const poly_model_desc *m, int F, int R);
+
+int poly_forward(const poly_model_desc *m, const poly_base_weights *base, const poly_lora_weights *lora,
+                 const poly_heads *heads, const void *frames, int F, const int32_t *row_offsets,
+                 const int32_t *adapter_ids, int R, float *out_logits, float *out_scores,
+                 float *out_merged, int K, int32_t *dev_status, void *workspace, size_t workspace_bytes,
+                 void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * poly_lora_linear -- one multi-adapter linear in isolation (Sec. 3.1: h = xW + xAB with the
+ * adapters applied side by side on a shared W).  Row-block b = (X block f, adapter k):
+ *       Y[b] = X[f] Wt^T + bias + scale * (X[f] At_k^T) Bt_k^T.
+ *   X [n_xblocks][T][Kdim] elt;  Wt [Ndim][Kdim] elt;  bias [Ndim] float, nullable;
+ *   At [N_ad][r][Kdim] elt;  Bt [N_ad][Ndim][r] elt;
+ *   row_offsets [n_xblocks+1], adapter_ids [R] as in poly_forward (R = host upper bound);
+ *   Y [R][T][Ndim] elt.   The base product X[f] Wt^T is computed once per X block and reused by
+ *   all row-blocks of that block.
+ *   workspace >= poly_lora_linear_workspace_bytes(...) bytes.
+ */
+size_t poly_lora_linear_workspace_bytes(int n_xblocks, int T, int r, int R, int dtype);
+
+int poly_lora_linear(const void *X, int n_xblocks, int T, int Kdim, const void *Wt, const float *bias,
+                     int Ndim, const void *At, const void *Bt, int n_adapters, int r, float scale,
+                     const int32_t *row_offsets, const int32_t *adapter_ids, int R, void *Y, int dtype,
+                     int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POLY_H */

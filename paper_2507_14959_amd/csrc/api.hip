@@ -1,0 +1,272 @@
+// C-ABI entry points: argument checks, workspace carving and the launch sequence of the forward.
+#include "poly_dev.h"
+
+namespace {
+
+inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+inline size_t elt_size(int dtype) { return dtype == POLY_BF16 ? 2 : 4; }
+inline int rank_pad(int r) { return (r + 15) / 16 * 16; }
+
+struct Carver {
+    char *base;
+    size_t off;
+    template <typename T> T *take(size_t bytes)
+    {
+        T *p = base ? (T *)(base + off) : nullptr;
+        off = align_up(off + bytes);
+        return p;
+    }
+};
+
+struct ForwardWs {
+    PolyMeta *meta;
+    int32_t *frame_of_row, *adapter_of_row;
+    float *xa, *xb;  // residual streams: per frame (shared layers), per row-block (adapted layers)
+    void *u, *qkv, *o, *h, *S, *patches;
+    size_t bytes;
+};
+
+ForwardWs carve_forward(const poly_model_desc *m, int F, int R, void *base)
+{
+    const size_t T = 1 + (size_t)(m->H / m->patch) * (m->W / m->patch), es = elt_size(m->dtype);
+    const size_t nb = (size_t)(F > R ? F : R), rows = nb * T;
+    Carver c{(char *)base, 0};
+    ForwardWs w;
+    w.meta = c.take<PolyMeta>(sizeof(PolyMeta));
+    w.frame_of_row = c.take<int32_t>(sizeof(int32_t) * (size_t)(R + 1));
+    w.adapter_of_row = c.take<int32_t>(sizeof(int32_t) * (size_t)(R + 1));
+    w.xa = c.take<float>(sizeof(float) * (size_t)F * T * m->D);
+    w.xb = c.take<float>(sizeof(float) * (size_t)R * T * m->D);
+    w.u = c.take<void>(es * rows * m->D);
+    w.qkv = c.take<void>(es * rows * 3 * m->D);
+    w.o = c.take<void>(es * rows * m->D);
+    w.h = c.take<void>(es * rows * m->Dm);
+    w.S = c.take<void>(es * (size_t)R * T * rank_pad(m->r));
+    w.patches = c.take<void>(es * (size_t)F * (T - 1) * 3 * m->patch * m->patch);
+    w.bytes = c.off;
+    return w;
+}
+
+int check_model(const poly_model_desc *m)
+{
+    if (!m) return POLY_EINVAL;
+    if (m->dtype != POLY_F32 && m->dtype != POLY_BF16) return POLY_EINVAL;
+    if (m->patch <= 0 || m->H <= 0 || m->W <= 0 || m->H % m->patch || m->W % m->patch) return POLY_EINVAL;
+    if (m->heads <= 0 || m->D != m->heads * POLY_HEAD_DIM || m->Dm <= 0 || m->L <= 0) return POLY_EINVAL;
+    if (m->L0 < 0 || m->L0 > m->L) return POLY_EINVAL;
+    if (m->r <= 0 || m->r > POLY_MAX_RANK || m->n_adapters <= 0 || m->C <= 0 || m->C > POLY_MAX_HEAD_CLASSES) return POLY_EINVAL;
+    if (m->targets & ~15) return POLY_EINVAL;
+    const int T = 1 + (m->H / m->patch) * (m->W / m->patch);
+    if (m->dtype == POLY_BF16) {
+        // 16-byte vector loads along the contraction index; attention keeps a block's keys in LDS
+        if (m->Dm % 8 || (3 * m->patch * m->patch) % 8 || T > 224) return POLY_EINVAL;
+    } else {
+        if (m->Dm % 4 || (3 * m->patch * m->patch) % 4) return POLY_EINVAL;
+    }
+    return POLY_OK;
+}
+
+#define POLY_TRY(expr)                  \
+    do {                                \
+        const int rc_ = (expr);         \
+        if (rc_ != POLY_OK) return rc_; \
+    } while (0)
+
+}  // namespace
+
+extern "C" const char *poly_status_string(int status)
+{
+    switch (status) {
+    case POLY_OK: return "ok";
+    case POLY_EINVAL: return "invalid argument";
+    case POLY_ERANGE: return "adapter id or row offsets out of range";
+    case POLY_ECAP: return "output or workspace too small";
+    case POLY_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+extern "C" size_t poly_forward_workspace_bytes(const poly_model_desc *m, int F, int R)
+{
+    if (check_model(m) != POLY_OK || F < 0 || R < 0) return 0;
+    return carve_forward(m, F, R, nullptr).bytes;
+}
+
+extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *base, const poly_lora_weights *lora,
+                            const poly_heads *heads, const void *frames, int F, const int32_t *row_offsets,
+                            const int32_t *adapter_ids, int R, float *out_logits, float *out_scores, float *out_merged, int K,
+                            int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream)
+{
+    POLY_TRY(check_model(m));
+    if (!base || !heads || F < 0 || R < 0) return POLY_EINVAL;
+    if (F == 0) return POLY_OK;
+    if (!frames || !row_offsets || (R > 0 && (!adapter_ids || !out_scores))) return POLY_EINVAL;
+    if (!base->patch_w || !base->patch_b || !base->cls || !base->pos || !base->ln1_g || !base->ln1_b || !base->qkv_w ||
+        !base->qkv_b || !base->proj_w || !base->proj_b || !base->ln2_g || !base->ln2_b || !base->fc1_w || !base->fc1_b ||
+        !base->fc2_w || !base->fc2_b || !base->lnf_g || !base->lnf_b || !heads->head_w || !heads->head_b)
+        return POLY_EINVAL;
+    if (out_merged && (!heads->class_map || K <= 0)) return POLY_EINVAL;
+    const bool adapted = m->L0 < m->L;
+    for (int t = 0; t < 4; ++t)
+        if (adapted && (m->targets & (1 << t)) && (!lora || !lora->At[t] || !lora->Bt[t])) return POLY_EINVAL;
+    if (((uintptr_t)workspace & 255) != 0 || !workspace) return POLY_EINVAL;
+    const ForwardWs w = carve_forward(m, F, R, workspace);
+    if (workspace_bytes < w.bytes) return POLY_ECAP;
+
+    hipStream_t st = (hipStream_t)stream;
+    const int dt = m->dtype, D = m->D, Dm = m->Dm, T = 1 + (m->H / m->patch) * (m->W / m->patch), pd = 3 * m->patch * m->patch;
+    const int RP = rank_pad(m->r);
+    const size_t es = elt_size(dt);
+    const int *R_dev = &w.meta->R;
+
+    POLY_TRY(launch_prep(row_offsets, adapter_ids, F, R, m->n_adapters, w.meta, w.frame_of_row, w.adapter_of_row, dev_status, st));
+
+    // tokens: x[f][0] = cls + pos[0]; x[f][1 + t] = patch_t W_pe + b_pe + pos[1 + t]
+    POLY_TRY(launch_im2col(frames, w.patches, F, m->H, m->W, m->patch, dt, st));
+    POLY_TRY(launch_cls(w.xa, base->cls, base->pos, F, T, D, st));
+    {
+        GemmArgs g = {};
+        g.A = w.patches; g.Wt = base->patch_w; g.bias = base->patch_b;
+        g.T = T - 1; g.K = pd; g.N = D; g.n_in = F;
+        g.mode = EPI_RESID; g.out = w.xa; g.Tout = T; g.t_off = 1; g.pos = base->pos;
+        POLY_TRY(launch_gemm(g, dt, st));
+    }
+
+    for (int l = 0; l < m->L; ++l) {
+        const bool lora_on = l >= m->L0 && R > 0;
+        if (l >= m->L0 && R == 0) break;
+        const bool fan = l == m->L0;           // first adapted layer: frames fan out into row-blocks
+        const bool branch = l > m->L0;         // residual stream already per row-block
+        float *x_in = branch ? w.xb : w.xa;
+        float *x_out = l >= m->L0 ? w.xb : w.xa;
+        const int nb = branch ? R : F;         // blocks of the LayerNorm-1 input
+        const int *nb_dev = branch ? R_dev : nullptr;
+        const int n_out = l >= m->L0 ? R : F;  // blocks after the qkv linear
+        const int *n_out_dev = l >= m->L0 ? R_dev : nullptr;
+
+        auto lora_ptr = [&](const void *stack, int t, size_t din, size_t dout, bool is_A) -> const void * {
+            (void)t;
+            const size_t per_layer = (size_t)m->n_adapters * m->r * (is_A ? din : dout);
+            return (const char *)stack + es * per_layer * (size_t)(l - m->L0);
+        };
+        auto use = [&](int t) { return lora_on && (m->targets & (1 << t)); };
+
+        // ---- attention half
+        POLY_TRY(launch_layernorm(x_in, w.u, base->ln1_g + (size_t)l * D, base->ln1_b + (size_t)l * D, D, m->ln_eps, T, nb, nb_dev, dt, st));
+        {
+            GemmArgs g = {};
+            g.A = w.u; g.Wt = (const char *)base->qkv_w + es * (size_t)l * 3 * D * D; g.bias = base->qkv_b + (size_t)l * 3 * D;
+            g.T = T; g.K = D; g.N = 3 * D; g.n_in = nb; g.n_in_dev = fan ? &w.meta->F_ok : nb_dev;
+            g.out_off = fan ? row_offsets : nullptr;
+            if (use(0)) {
+                const void *At = lora_ptr(lora->At[0], 0, D, 3 * D, true), *Bt = lora_ptr(lora->Bt[0], 0, D, 3 * D, false);
+                POLY_TRY(launch_shrink(w.u, T, D, At, m->r, RP, m->lora_scale, R, R_dev, fan ? w.frame_of_row : nullptr, w.adapter_of_row, w.S, dt, st));
+                g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = m->r; g.adapter_of_out = w.adapter_of_row;
+            }
+            g.mode = EPI_STORE; g.out = w.qkv; g.Tout = T;
+            POLY_TRY(launch_gemm(g, dt, st));
+        }
+        POLY_TRY(launch_attention(w.qkv, w.o, T, D, m->heads, n_out, n_out_dev, dt, st));
+        {
+            GemmArgs g = {};
+            g.A = w.o; g.Wt = (const char *)base->proj_w + es * (size_t)l * D * D; g.bias = base->proj_b + (size_t)l * D;
+            g.T = T; g.K = D; g.N = D; g.n_in = n_out; g.n_in_dev = n_out_dev;
+            if (use(1)) {
+                const void *At = lora_ptr(lora->At[1], 1, D, D, true), *Bt = lora_ptr(lora->Bt[1], 1, D, D, false);
+                POLY_TRY(launch_shrink(w.o, T, D, At, m->r, RP, m->lora_scale, R, R_dev, nullptr, w.adapter_of_row, w.S, dt, st));
+                g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = m->r; g.adapter_of_out = w.adapter_of_row;
+            }
+            g.mode = EPI_RESID; g.out = x_out; g.Tout = T; g.res = x_in; g.res_block_of_out = fan ? w.frame_of_row : nullptr;
+            POLY_TRY(launch_gemm(g, dt, st));
+        }
+        // ---- MLP half (x_out holds the stream from here on)
+        POLY_TRY(launch_layernorm(x_out, w.u, base->ln2_g + (size_t)l * D, base->ln2_b + (size_t)l * D, D, m->ln_eps, T, n_out, n_out_dev, dt, st));
+        {
+            GemmArgs g = {};
+            g.A = w.u; g.Wt = (const char *)base->fc1_w + es * (size_t)l * Dm * D; g.bias = base->fc1_b + (size_t)l * Dm;
+            g.T = T; g.K = D; g.N = Dm; g.n_in = n_out; g.n_in_dev = n_out_dev;
+            if (use(2)) {
+                const void *At = lora_ptr(lora->At[2], 2, D, Dm, true), *Bt = lora_ptr(lora->Bt[2], 2, D, Dm, false);
+                POLY_TRY(launch_shrink(w.u, T, D, At, m->r, RP, m->lora_scale, R, R_dev, nullptr, w.adapter_of_row, w.S, dt, st));
+                g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = m->r; g.adapter_of_out = w.adapter_of_row;
+            }
+            g.mode = EPI_GELU; g.out = w.h; g.Tout = T;
+            POLY_TRY(launch_gemm(g, dt, st));
+        }
+        {
+            GemmArgs g = {};
+            g.A = w.h; g.Wt = (const char *)base->fc2_w + es * (size_t)l * D * Dm; g.bias = base->fc2_b + (size_t)l * D;
+            g.T = T; g.K = Dm; g.N = D; g.n_in = n_out; g.n_in_dev = n_out_dev;
+            if (use(3)) {
+                const void *At = lora_ptr(lora->At[3], 3, Dm, D, true), *Bt = lora_ptr(lora->Bt[3], 3, Dm, D, false);
+                POLY_TRY(launch_shrink(w.h, T, Dm, At, m->r, RP, m->lora_scale, R, R_dev, nullptr, w.adapter_of_row, w.S, dt, st));
+                g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = m->r; g.adapter_of_out = w.adapter_of_row;
+            }
+            g.mode = EPI_RESID; g.out = x_out; g.Tout = T; g.res = x_out;
+            POLY_TRY(launch_gemm(g, dt, st));
+        }
+    }
+
+    if (R > 0) {
+        POLY_TRY(launch_head(adapted ? w.xb : w.xa, adapted ? nullptr : w.frame_of_row, T, D, base->lnf_g, base->lnf_b, m->ln_eps,
+                             heads->head_w, heads->head_b, m->C, w.adapter_of_row, w.meta, R, out_logits, out_scores, dt, st));
+    }
+    if (out_merged)
+        POLY_TRY(launch_merge(out_scores, w.frame_of_row, w.adapter_of_row, heads->class_map, m->C, K, w.meta, F, R, out_merged, st));
+    return POLY_OK;
+}
+
+// ------------------------------------------------------------------ isolated multi-LoRA linear
+
+namespace {
+struct LinearWs {
+    PolyMeta *meta;
+    int32_t *frame_of_row, *adapter_of_row;
+    void *S;
+    size_t bytes;
+};
+LinearWs carve_linear(int T, int r, int R, int dtype, void *base)
+{
+    Carver c{(char *)base, 0};
+    LinearWs w;
+    w.meta = c.take<PolyMeta>(sizeof(PolyMeta));
+    w.frame_of_row = c.take<int32_t>(sizeof(int32_t) * (size_t)(R + 1));
+    w.adapter_of_row = c.take<int32_t>(sizeof(int32_t) * (size_t)(R + 1));
+    w.S = c.take<void>(elt_size(dtype) * (size_t)R * T * rank_pad(r));
+    w.bytes = c.off;
+    return w;
+}
+}  // namespace
+
+extern "C" size_t poly_lora_linear_workspace_bytes(int n_xblocks, int T, int r, int R, int dtype)
+{
+    if (n_xblocks < 0 || T <= 0 || r <= 0 || R < 0 || (dtype != POLY_F32 && dtype != POLY_BF16)) return 0;
+    return carve_linear(T, r, R, dtype, nullptr).bytes;
+}
+
+extern "C" int poly_lora_linear(const void *X, int n_xblocks, int T, int Kdim, const void *Wt, const float *bias, int Ndim,
+                                const void *At, const void *Bt, int n_adapters, int r, float scale, const int32_t *row_offsets,
+                                const int32_t *adapter_ids, int R, void *Y, int dtype, int32_t *dev_status, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    if (dtype != POLY_F32 && dtype != POLY_BF16) return POLY_EINVAL;
+    if (n_xblocks < 0 || T <= 0 || Kdim <= 0 || Ndim <= 0 || n_adapters <= 0 || r <= 0 || r > POLY_MAX_RANK || R < 0) return POLY_EINVAL;
+    if (Kdim % (dtype == POLY_BF16 ? 8 : 4)) return POLY_EINVAL;
+    if (n_xblocks == 0) return POLY_OK;
+    if (!X || !Wt || !At || !Bt || !row_offsets || (R > 0 && (!adapter_ids || !Y))) return POLY_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0) return POLY_EINVAL;
+    const LinearWs w = carve_linear(T, r, R, dtype, workspace);
+    if (workspace_bytes < w.bytes) return POLY_ECAP;
+    hipStream_t st = (hipStream_t)stream;
+    const int RP = rank_pad(r);
+
+    POLY_TRY(launch_prep(row_offsets, adapter_ids, n_xblocks, R, n_adapters, w.meta, w.frame_of_row, w.adapter_of_row, dev_status, st));
+    if (R == 0) return POLY_OK;
+    POLY_TRY(launch_shrink(X, T, Kdim, At, r, RP, scale, R, &w.meta->R, w.frame_of_row, w.adapter_of_row, w.S, dtype, st));
+    GemmArgs g = {};
+    g.A = X; g.Wt = Wt; g.bias = bias; g.T = T; g.K = Kdim; g.N = Ndim;
+    g.n_in = n_xblocks; g.n_in_dev = &w.meta->F_ok; g.out_off = row_offsets;
+    g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = r; g.adapter_of_out = w.adapter_of_row;
+    g.mode = EPI_STORE; g.out = Y; g.Tout = T;
+    return launch_gemm(g, dtype, st);
+}

@@ -1,0 +1,210 @@
+// Fused softmax attention of one (token block, head) per workgroup; head width 64.
+//
+// bf16: K and V^T of the head are staged once in LDS.  Each wave owns 32 queries at a time and computes
+// S^T = K Q^T on the MFMA (keys down the rows, so every lane holds all scores of ONE query), takes the
+// softmax over its registers in fp32, and feeds the unnormalised probabilities straight back as the B
+// operand of O^T = V^T P^T -- the accumulator layout of S^T is already a valid B layout once the keys of
+// each 16-key step are read from V^T in the matching order.  1/sum is applied per lane at the end.
+// fp32: one thread per query with an online softmax, keys and values streamed through LDS.
+#include "poly_dev.h"
+
+namespace {
+
+constexpr float LOG2E = 1.4426950408889634f;
+
+template <int NKT>  // 32-key tiles: T <= 32 * NKT
+__global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_t *out, int T, int D, int heads, int n_blocks,
+                                                        const int *n_blocks_dev)
+{
+    constexpr int TKP = NKT * 32;
+    constexpr int KS = 64 + 8;    // Ks row stride (elements): 144 B, 16-byte aligned
+    constexpr int VS = TKP + 8;   // Vt row stride: multiple of 8 elements
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[TKP * KS];
+    __shared__ __attribute__((aligned(16))) bf16_t Vt[64 * VS];
+
+    const int nb = n_blocks_dev ? min(*n_blocks_dev, n_blocks) : n_blocks;
+    const int b = blockIdx.x / heads, hd = blockIdx.x % heads;
+    if (b >= nb) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lm = lane & 31, lh = lane >> 5;
+    const size_t ld = (size_t)3 * D;
+    const bf16_t *base = qkv + (size_t)b * T * ld + hd * 64;
+    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+
+    for (int v = tid; v < TKP * 8; v += 256) {
+        const int key = v >> 3, c8 = (v & 7) * 8;
+        bf16x8 kk = zero8, vv = zero8;
+        if (key < T) {
+            kk = *(const bf16x8 *)(base + (size_t)key * ld + D + c8);
+            vv = *(const bf16x8 *)(base + (size_t)key * ld + 2 * D + c8);
+        }
+        *(bf16x8 *)(Ks + key * KS + c8) = kk;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) Vt[(c8 + q) * VS + key] = vv[q];
+    }
+    __syncthreads();
+
+    const int nq = (T + 31) / 32;
+    for (int qs = wave; qs < nq; qs += 4) {
+        const int query = qs * 32 + lm;
+        bf16x8 qf[4];
+#pragma unroll
+        for (int ds = 0; ds < 4; ++ds)
+            qf[ds] = query < T ? *(const bf16x8 *)(base + (size_t)query * ld + ds * 16 + lh * 8) : zero8;
+
+        // S^T tile kt: rows = keys kt*32 + 8*(e/4) + 4*lh + e%4, column = this lane's query
+        f32x16 s[NKT];
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[kt][e] = 0.f;
+#pragma unroll
+            for (int ds = 0; ds < 4; ++ds) {
+                const bf16x8 kf = *(const bf16x8 *)(Ks + (kt * 32 + lm) * KS + ds * 16 + lh * 8);
+                s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ds], s[kt], 0, 0, 0);
+            }
+        }
+
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = kt * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+                s[kt][e] = key < T ? s[kt][e] : -INFINITY;
+                mx = fmaxf(mx, s[kt][e]);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float sc = 0.125f * LOG2E;  // 1/sqrt(64), folded into the base-2 exponent
+        float sum = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float p = exp2f((s[kt][e] - mx) * sc);
+                s[kt][e] = p;
+                sum += p;
+            }
+        sum += __shfl_xor(sum, 32, 64);
+
+        // O^T = V^T P^T: rows = head columns, column = this lane's query
+        f32x16 o[2];
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+            for (int hs = 0; hs < 2; ++hs) {
+                bf16x8 pf;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) pf[q] = (bf16_t)s[kt][hs * 8 + q];
+                // slots 0..3 = keys kbase + 4*lh + 0..3, slots 4..7 = keys kbase + 8 + 4*lh + 0..3
+                const int kbase = kt * 32 + hs * 16 + 4 * lh;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    const bf16_t *vr = Vt + (dt * 32 + lm) * VS + kbase;
+                    const bf16x4 lo = *(const bf16x4 *)vr, hi = *(const bf16x4 *)(vr + 8);
+                    const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[dt], 0, 0, 0);
+                }
+            }
+
+        if (query < T) {
+            const float inv = 1.0f / sum;
+            bf16_t *orow = out + ((size_t)b * T + query) * D + hd * 64;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4 w;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) w[q] = (bf16_t)(o[dt][g * 4 + q] * inv);
+                    *(bf16x4 *)(orow + dt * 32 + 8 * g + 4 * lh) = w;
+                }
+        }
+    }
+}
+
+// fp32 path: keys and values go through LDS in chunks of 64; each thread keeps q, the running
+// maximum, the running sum and the 64 output columns of one query.
+__global__ __launch_bounds__(256) void attn_f32_kernel(const float *qkv, float *out, int T, int D, int heads, int n_blocks,
+                                                       const int *n_blocks_dev)
+{
+    __shared__ float Ks[64][65];
+    __shared__ float Vs[64][65];
+    const int nb = n_blocks_dev ? min(*n_blocks_dev, n_blocks) : n_blocks;
+    const int b = blockIdx.x / heads, hd = blockIdx.x % heads;
+    if (b >= nb) return;
+    const int tid = threadIdx.x;
+    const size_t ld = (size_t)3 * D;
+    const float *base = qkv + (size_t)b * T * ld + hd * 64;
+
+    for (int q0 = 0; q0 < T; q0 += 256) {
+        const int query = q0 + tid;
+        float q[64], o[64];
+        float mx = -INFINITY, sum = 0.f;
+#pragma unroll
+        for (int c = 0; c < 64; ++c) { q[c] = query < T ? base[(size_t)query * ld + c] * 0.125f : 0.f; o[c] = 0.f; }
+        for (int k0 = 0; k0 < T; k0 += 64) {
+            __syncthreads();
+            for (int v = tid; v < 64 * 64; v += 256) {
+                const int key = v >> 6, c = v & 63;
+                const bool ok = k0 + key < T;
+                Ks[key][c] = ok ? base[(size_t)(k0 + key) * ld + D + c] : 0.f;
+                Vs[key][c] = ok ? base[(size_t)(k0 + key) * ld + 2 * D + c] : 0.f;
+            }
+            __syncthreads();
+            const int kn = min(64, T - k0);
+            for (int key = 0; key < kn; ++key) {
+                float sdot = 0.f;
+#pragma unroll
+                for (int c = 0; c < 64; ++c) sdot = fmaf(q[c], Ks[key][c], sdot);
+                const float nm = fmaxf(mx, sdot);
+                const float corr = expf(mx - nm), p = expf(sdot - nm);
+                sum = sum * corr + p;
+#pragma unroll
+                for (int c = 0; c < 64; ++c) o[c] = fmaf(p, Vs[key][c], o[c] * corr);
+                mx = nm;
+            }
+        }
+        if (query < T) {
+            const float inv = 1.0f / sum;
+            float *orow = out + ((size_t)b * T + query) * D + hd * 64;
+#pragma unroll
+            for (int c = 0; c < 64; ++c) orow[c] = o[c] * inv;
+        }
+    }
+}
+
+template <int NKT>
+void launch_bf16(const void *qkv, void *out, int T, int D, int heads, int n_blocks, const int *n_blocks_dev, hipStream_t st)
+{
+    hipLaunchKernelGGL(attn_bf16_kernel<NKT>, dim3((unsigned)(n_blocks * heads)), dim3(256), 0, st, (const bf16_t *)qkv, (bf16_t *)out, T, D,
+                       heads, n_blocks, n_blocks_dev);
+}
+
+}  // namespace
+
+int launch_attention(const void *qkv, void *out, int T, int D, int heads, int n_blocks, const int *n_blocks_dev, int dtype,
+                     hipStream_t st)
+{
+    if (n_blocks == 0) return POLY_OK;
+    if (D != heads * 64) return POLY_EINVAL;
+    if (dtype == POLY_BF16) {
+        switch ((T + 31) / 32) {
+        case 1: launch_bf16<1>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
+        case 2: launch_bf16<2>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
+        case 3: launch_bf16<3>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
+        case 4: launch_bf16<4>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
+        case 5: launch_bf16<5>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
+        case 6: launch_bf16<6>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
+        case 7: launch_bf16<7>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
+        default: return POLY_EINVAL;  // bf16 attention holds all keys of a block in 64 KB of LDS: T <= 224
+        }
+    } else {
+        hipLaunchKernelGGL(attn_f32_kernel, dim3((unsigned)(n_blocks * heads)), dim3(256), 0, st, (const float *)qkv, (float *)out, T, D, heads,
+                           n_blocks, n_blocks_dev);
+    }
+    return hipGetLastError() == hipSuccess ? POLY_OK : POLY_EHIP;
+}

@@ -1,0 +1,96 @@
+// Device-side helpers shared by the libpoly kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/poly.h"
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#define POLY_WAVE 64
+
+// Device-visible bookkeeping at the head of the workspace.
+struct PolyMeta {
+    int32_t R;       // row_offsets[F] as read on the device (0 when the inputs are rejected)
+    int32_t status;  // POLY_OK or POLY_ERANGE
+    int32_t F_ok;    // number of frames, or 0 when the inputs are rejected
+    int32_t pad[61];
+};
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+template <typename T> __device__ __forceinline__ float to_f32(T v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v) { return (T)v; }
+
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
+
+// ---- stage launchers (defined in the .hip files, used by the entry points in api.hip) ----
+
+enum { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2 };
+
+// C = A Wt^T with per-block structure.  Rows come in blocks of T; input block xb feeds the output
+// blocks [out_off[xb], out_off[xb+1]) (or block xb itself when out_off is null).  Each output block ob
+// may add its own low-rank term S[ob] Bt[adapter_of_out[ob]]^T before the epilogue.
+struct GemmArgs {
+    const void *A;    // elt [n_in*T][K]
+    const void *Wt;   // elt [N][K]
+    const float *bias;  // [N] or null
+    int T, K, N;
+    int n_in;             // upper bound of the number of input blocks (grid size)
+    const int *n_in_dev;  // true count on the device, or null (= n_in)
+    const int *out_off;   // [n_in+1] or null
+    const void *S;        // elt [n_out*T][RP], zero padded to RP columns, or null
+    int RP;
+    const void *Bt;       // elt [n_adapters][N][r]
+    int r;
+    const int *adapter_of_out;  // [n_out], < 0 = no adapter
+    int mode;             // EPI_*
+    void *out;            // EPI_STORE / EPI_GELU: elt [n_out*Tout][N]; EPI_RESID: float, same shape
+    int Tout, t_off;      // output row of (ob, t) is ob*Tout + t_off + t
+    const float *res;     // EPI_RESID: float [..*Tout][N] added (row res_block*Tout + t_off + t), or null
+    const int *res_block_of_out;  // null = ob
+    const float *pos;     // EPI_RESID: float [Tout][N] added (row t_off + t), or null
+};
+
+int launch_gemm(const GemmArgs &g, int dtype, hipStream_t st);
+
+// y = LayerNorm(x) row-wise; x float [n*T][D] -> elt [n*T][D]
+int launch_layernorm(const float *x, void *y, const float *gain, const float *shift, int D, float eps, int T,
+                     int n_blocks, const int *n_blocks_dev, int dtype, hipStream_t st);
+
+// S[ob] = scale * X[in_block_of_out[ob]] At[adapter_of_out[ob]]^T, zero padded to RP columns
+int launch_shrink(const void *X, int T, int K, const void *At, int r, int RP, float scale, int n_out,
+                  const int *n_out_dev, const int *in_block_of_out, const int *adapter_of_out, void *S, int dtype,
+                  hipStream_t st);
+
+// softmax attention of every (block, head); qkv elt [n*T][3D] -> out elt [n*T][D]
+int launch_attention(const void *qkv, void *out, int T, int D, int heads, int n_blocks, const int *n_blocks_dev,
+                     int dtype, hipStream_t st);
+
+// ---- bookkeeping and row-wise stages (rowops.hip) ----
+int launch_prep(const int32_t *row_offsets, const int32_t *adapter_ids, int F, int R_cap, int n_adapters, PolyMeta *meta,
+                int32_t *frame_of_row, int32_t *adapter_of_row, int32_t *dev_status, hipStream_t st);
+int launch_im2col(const void *frames, void *patches, int F, int H, int W, int p, int dtype, hipStream_t st);
+int launch_cls(float *x, const float *cls, const float *pos, int F, int T, int D, hipStream_t st);
+int launch_head(const float *x, const int *src_block_of_row, int T, int D, const float *gain, const float *shift, float eps,
+                const void *head_w, const float *head_b, int C, const int *adapter_of_row, const PolyMeta *meta, int R_cap,
+                float *logits, float *scores, int dtype, hipStream_t st);
+int launch_merge(const float *scores, const int *frame_of_row, const int *adapter_of_row, const int32_t *class_map, int C, int K,
+                 const PolyMeta *meta, int F, int R_cap, float *merged, hipStream_t st);

@@ -1,0 +1,294 @@
+// Row-wise and bookkeeping kernels of the forward: CSR validation, patch gathering, LayerNorm,
+// LoRA shrink (x A_k), per-adapter heads with sigmoid, and the optional merge to label space.
+#include "poly_dev.h"
+
+namespace {
+
+// ------------------------------------------------------------------ CSR check + row maps
+// One block.  Validates row_offsets / adapter_ids against (F, R_cap, n_adapters) and builds
+// frame_of_row / adapter_of_row.  On any violation nothing downstream runs (meta->R = 0).
+__global__ void prep_kernel(const int32_t *row_offsets, const int32_t *adapter_ids, int F, int R_cap, int n_adapters,
+                            PolyMeta *meta, int32_t *frame_of_row, int32_t *adapter_of_row, int32_t *dev_status)
+{
+    __shared__ int bad;
+    if (threadIdx.x == 0) bad = 0;
+    __syncthreads();
+    const int R = row_offsets[F];
+    if (row_offsets[0] != 0 || R < 0 || R > R_cap) {
+        if (threadIdx.x == 0) bad = 1;
+    } else {
+        for (int f = threadIdx.x; f < F; f += blockDim.x) {
+            const int a = row_offsets[f], b = row_offsets[f + 1];
+            if (a > b || a < 0 || b > R) { bad = 1; continue; }
+            for (int i = a; i < b; ++i) {
+                const int k = adapter_ids[i];
+                if (k < 0 || k >= n_adapters) bad = 1;
+                frame_of_row[i] = f;
+                adapter_of_row[i] = k;
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        meta->R = bad ? 0 : R;
+        meta->F_ok = bad ? 0 : F;
+        meta->status = bad ? POLY_ERANGE : POLY_OK;
+        if (dev_status) *dev_status = meta->status;
+    }
+}
+
+// ------------------------------------------------------------------ patch gathering
+// patches[(f*P + ty*gw + tx)][(i*p + j)*3 + c] = frame[f][ty*p + i][tx*p + j][c]; a run of 3p values
+// (fixed i) is contiguous in the NHWC frame.
+template <typename T>
+__global__ void im2col_kernel(const T *frames, T *patches, int F, int H, int W, int p)
+{
+    const int gw = W / p, gh = H / p, run = 3 * p;
+    const size_t total = (size_t)F * gh * gw * p * run;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        size_t q = idx;
+        const int e = q % run; q /= run;
+        const int i = q % p; q /= p;
+        const int tx = q % gw; q /= gw;
+        const int ty = q % gh; const size_t f = q / gh;
+        patches[idx] = frames[((f * H + (size_t)ty * p + i) * W + (size_t)tx * p) * 3 + e];
+    }
+}
+
+// x[f][0][:] = cls + pos[0]
+__global__ void cls_kernel(float *x, const float *cls, const float *pos, int F, int T, int D)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < F * D) {
+        const int f = idx / D, c = idx % D;
+        x[(size_t)f * T * D + c] = cls[c] + pos[c];
+    }
+}
+
+// ------------------------------------------------------------------ LayerNorm
+// One wave per row; fp32 statistics (mean, then centred second moment), output in the activation type.
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_kernel(const float *x, T *y, const float *gain, const float *shift, int D,
+                                                        float eps, int rows_per_block, int n_blocks, const int *n_blocks_dev)
+{
+    const int nb = n_blocks_dev ? min(*n_blocks_dev, n_blocks) : n_blocks;
+    const size_t rows = (size_t)nb * rows_per_block;
+    const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int lane = threadIdx.x & 63;
+    const float *xr = x + row * D;
+    float s = 0.f;
+    for (int k = lane; k < D; k += 64) s += xr[k];
+    const float mean = wave_sum(s) / D;
+    float v = 0.f;
+    for (int k = lane; k < D; k += 64) { const float d = xr[k] - mean; v += d * d; }
+    const float inv = rsqrtf(wave_sum(v) / D + eps);
+    T *yr = y + row * D;
+    for (int k = lane; k < D; k += 64) yr[k] = from_f32<T>((xr[k] - mean) * inv * gain[k] + shift[k]);
+}
+
+// ------------------------------------------------------------------ LoRA shrink
+// bf16: one wave per 32 rows of one output block; S = scale * X At_k^T on the MFMA, operands read straight
+// from global memory (each lane 16 contiguous bytes along K), result zero padded to RP columns.
+__global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *X, int T, int K, const bf16_t *At, int r, int RP,
+                                                          float scale, int n_out, const int *n_out_dev,
+                                                          const int *in_block_of_out, const int *adapter_of_out, bf16_t *S)
+{
+    const int subs = (T + 31) / 32;
+    const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int ob = w / subs, sub = w % subs;
+    const int n = n_out_dev ? min(*n_out_dev, n_out) : n_out;
+    if (ob >= n) return;
+    const int k_ad = adapter_of_out[ob];
+    if (k_ad < 0) return;
+    const int xb = in_block_of_out ? in_block_of_out[ob] : ob;
+    const int lane = threadIdx.x & 63, lm = lane & 31, lh = lane >> 5;
+    const int t = sub * 32 + lm;
+    const bf16_t *xr = X + ((size_t)xb * T + min(t, T - 1)) * K;
+    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int j0 = 0; j0 < RP; j0 += 32) {
+        const int j = j0 + lm;
+        const bf16_t *ar = At + ((size_t)k_ad * r + min(j, r - 1)) * K;
+        f32x16 acc;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+        for (int k0 = 0; k0 < K; k0 += 16) {
+            const int k = k0 + lh * 8;
+            const bool kin = k + 8 <= K;
+            const bf16x8 fa = (t < T && kin) ? *(const bf16x8 *)(xr + k) : zero8;
+            const bf16x8 fb = (j < r && kin) ? *(const bf16x8 *)(ar + k) : zero8;
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
+        }
+        if (j < RP) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int tt = sub * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+                if (tt < T) S[((size_t)ob * T + tt) * RP + j] = (bf16_t)(scale * acc[e]);
+            }
+        }
+    }
+}
+
+// fp32: one thread per (row, rank)
+__global__ void shrink_f32_kernel(const float *X, int T, int K, const float *At, int r, int RP, float scale, int n_out,
+                                  const int *n_out_dev, const int *in_block_of_out, const int *adapter_of_out, float *S)
+{
+    const int n = n_out_dev ? min(*n_out_dev, n_out) : n_out;
+    const size_t total = (size_t)n * T * RP;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int j = idx % RP;
+        const size_t row = idx / RP;
+        const int ob = row / T, t = row % T;
+        const int k_ad = adapter_of_out[ob];
+        float acc = 0.f;
+        if (k_ad >= 0 && j < r) {
+            const int xb = in_block_of_out ? in_block_of_out[ob] : ob;
+            const float *xr = X + ((size_t)xb * T + t) * K;
+            const float *ar = At + ((size_t)k_ad * r + j) * K;
+            for (int k = 0; k < K; ++k) acc = fmaf(xr[k], ar[k], acc);
+        }
+        S[idx] = scale * acc;
+    }
+}
+
+// ------------------------------------------------------------------ heads
+// One wave per row-block: z = LN(x[src][0][:]); logits = z H_k + hb_k; scores = sigmoid(logits).
+template <typename T>
+__global__ __launch_bounds__(64) void head_kernel(const float *x, const int *src_block_of_row, int Tn, int D, const float *gain,
+                                                  const float *shift, float eps, const T *head_w, const float *head_b, int C,
+                                                  const int *adapter_of_row, const PolyMeta *meta, float *logits, float *scores)
+{
+    const int b = blockIdx.x;
+    if (b >= meta->R) return;
+    const int lane = threadIdx.x;
+    const int src = src_block_of_row ? src_block_of_row[b] : b;
+    const int k_ad = adapter_of_row[b];
+    const float *xr = x + (size_t)src * Tn * D;
+    float s = 0.f;
+    for (int k = lane; k < D; k += 64) s += xr[k];
+    const float mean = wave_sum(s) / D;
+    float v = 0.f;
+    for (int k = lane; k < D; k += 64) { const float d = xr[k] - mean; v += d * d; }
+    const float inv = rsqrtf(wave_sum(v) / D + eps);
+    for (int c = 0; c < C; ++c) {
+        const T *hw = head_w + ((size_t)k_ad * C + c) * D;
+        float a = 0.f;
+        for (int k = lane; k < D; k += 64) a = fmaf((xr[k] - mean) * inv * gain[k] + shift[k], to_f32(hw[k]), a);
+        a = wave_sum(a);
+        if (lane == 0) {
+            const float lg = a + head_b[k_ad * C + c];
+            if (logits) logits[(size_t)b * C + c] = lg;
+            scores[(size_t)b * C + c] = 1.0f / (1.0f + expf(-lg));
+        }
+    }
+}
+
+// ------------------------------------------------------------------ merge to label space
+__global__ void zero_kernel(float *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0.f;
+}
+
+// scores are in (0, 1): the order of positive floats is the order of their bit patterns, so an integer
+// atomic max merges overlapping adapters without depending on arrival order
+__global__ void merge_kernel(const float *scores, const int *frame_of_row, const int *adapter_of_row, const int32_t *class_map,
+                             int C, int K, const PolyMeta *meta, float *merged)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= meta->R * C) return;
+    const int b = idx / C, c = idx % C;
+    const int cls = class_map[adapter_of_row[b] * C + c];
+    if (cls < 0 || cls >= K) return;
+    atomicMax((int *)(merged + (size_t)frame_of_row[b] * K + cls), __float_as_int(scores[idx]));
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+
+static inline int hip_ok() { return hipGetLastError() == hipSuccess ? POLY_OK : POLY_EHIP; }
+
+int launch_prep(const int32_t *row_offsets, const int32_t *adapter_ids, int F, int R_cap, int n_adapters, PolyMeta *meta,
+                int32_t *frame_of_row, int32_t *adapter_of_row, int32_t *dev_status, hipStream_t st)
+{
+    hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(256), 0, st, row_offsets, adapter_ids, F, R_cap, n_adapters, meta, frame_of_row,
+                       adapter_of_row, dev_status);
+    return hip_ok();
+}
+
+int launch_im2col(const void *frames, void *patches, int F, int H, int W, int p, int dtype, hipStream_t st)
+{
+    const size_t total = (size_t)F * H * W * 3;
+    if (total == 0) return POLY_OK;
+    const unsigned blocks = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
+    if (dtype == POLY_BF16)
+        hipLaunchKernelGGL(im2col_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t *)frames, (bf16_t *)patches, F, H, W, p);
+    else
+        hipLaunchKernelGGL(im2col_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float *)frames, (float *)patches, F, H, W, p);
+    return hip_ok();
+}
+
+int launch_cls(float *x, const float *cls, const float *pos, int F, int T, int D, hipStream_t st)
+{
+    if (F == 0) return POLY_OK;
+    hipLaunchKernelGGL(cls_kernel, dim3((F * D + 255) / 256), dim3(256), 0, st, x, cls, pos, F, T, D);
+    return hip_ok();
+}
+
+int launch_layernorm(const float *x, void *y, const float *gain, const float *shift, int D, float eps, int T, int n_blocks,
+                     const int *n_blocks_dev, int dtype, hipStream_t st)
+{
+    const size_t rows = (size_t)n_blocks * T;
+    if (rows == 0) return POLY_OK;
+    const unsigned blocks = (unsigned)((rows + 3) / 4);
+    if (dtype == POLY_BF16)
+        hipLaunchKernelGGL(layernorm_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, x, (bf16_t *)y, gain, shift, D, eps, T, n_blocks, n_blocks_dev);
+    else
+        hipLaunchKernelGGL(layernorm_kernel<float>, dim3(blocks), dim3(256), 0, st, x, (float *)y, gain, shift, D, eps, T, n_blocks, n_blocks_dev);
+    return hip_ok();
+}
+
+int launch_shrink(const void *X, int T, int K, const void *At, int r, int RP, float scale, int n_out, const int *n_out_dev,
+                  const int *in_block_of_out, const int *adapter_of_out, void *S, int dtype, hipStream_t st)
+{
+    if (n_out == 0) return POLY_OK;
+    if (dtype == POLY_BF16) {
+        if (K % 8 != 0) return POLY_EINVAL;
+        const int subs = (T + 31) / 32;
+        const unsigned blocks = (unsigned)(((size_t)n_out * subs + 3) / 4);
+        hipLaunchKernelGGL(shrink_bf16_kernel, dim3(blocks), dim3(256), 0, st, (const bf16_t *)X, T, K, (const bf16_t *)At, r, RP, scale, n_out,
+                           n_out_dev, in_block_of_out, adapter_of_out, (bf16_t *)S);
+    } else {
+        const size_t total = (size_t)n_out * T * RP;
+        const unsigned blocks = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
+        hipLaunchKernelGGL(shrink_f32_kernel, dim3(blocks), dim3(256), 0, st, (const float *)X, T, K, (const float *)At, r, RP, scale, n_out,
+                           n_out_dev, in_block_of_out, adapter_of_out, (float *)S);
+    }
+    return hip_ok();
+}
+
+int launch_head(const float *x, const int *src_block_of_row, int T, int D, const float *gain, const float *shift, float eps,
+                const void *head_w, const float *head_b, int C, const int *adapter_of_row, const PolyMeta *meta, int R_cap,
+                float *logits, float *scores, int dtype, hipStream_t st)
+{
+    if (R_cap == 0) return POLY_OK;
+    if (dtype == POLY_BF16)
+        hipLaunchKernelGGL(head_kernel<bf16_t>, dim3(R_cap), dim3(64), 0, st, x, src_block_of_row, T, D, gain, shift, eps,
+                           (const bf16_t *)head_w, head_b, C, adapter_of_row, meta, logits, scores);
+    else
+        hipLaunchKernelGGL(head_kernel<float>, dim3(R_cap), dim3(64), 0, st, x, src_block_of_row, T, D, gain, shift, eps,
+                           (const float *)head_w, head_b, C, adapter_of_row, meta, logits, scores);
+    return hip_ok();
+}
+
+int launch_merge(const float *scores, const int *frame_of_row, const int *adapter_of_row, const int32_t *class_map, int C, int K,
+                 const PolyMeta *meta, int F, int R_cap, float *merged, hipStream_t st)
+{
+    const size_t n = (size_t)F * K;
+    if (n == 0) return POLY_OK;
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((n + 255) / 256 > 4096 ? 4096 : (n + 255) / 256)), dim3(256), 0, st, merged, n);
+    if (R_cap > 0)
+        hipLaunchKernelGGL(merge_kernel, dim3((R_cap * C + 255) / 256), dim3(256), 0, st, scores, frame_of_row, adapter_of_row, class_map,
+                           C, K, meta, merged);
+    return hip_ok();
+}

@@ -1,0 +1,206 @@
+// Context detection (Alg. 2, Sec. 3.5): label threshold -> greedy cover by contexts in (size, id)
+// order -> CSR adapter sets.  Integer work on 64-bit sets, one workgroup per call: a batch is
+// F x K = 64 x 80 scores, so latency, not throughput, is what matters.
+//
+// Label sets are bitsets built with wave ballots (one 64-label word per ballot, coalesced score
+// reads).  Contexts are renumbered by scan position, so a context set is a 64-bit mask whose
+// ascending bit order IS the selection order.  Frames are covered in parallel (one thread each);
+// the reuse branches of Alg. 2 need the previous frame's result and are resolved by a short
+// sequential pass that only runs when a state is carried or context_copy is set.
+#include "poly_dev.h"
+
+namespace {
+
+constexpr int CH = 128;  // frames per pass
+constexpr int KWMAX = POLY_MAX_LABELS / 64;
+constexpr int MMAX = POLY_MAX_CONTEXTS;
+
+struct SelState {       // device image of (Y_{t-1}, S_{t-1})
+    int32_t valid, pad;
+    uint64_t set_ids;   // S_{t-1} as a mask over context ids
+    uint64_t labels[1]; // KW words
+};
+
+__global__ __launch_bounds__(256) void select_kernel(const float *scores, int F, int K, const uint8_t *member, int M, float theta,
+                                                     int context_copy, const float *acc, float tau, SelState *state,
+                                                     int32_t *row_offsets, int32_t *adapter_ids, int cap, int32_t *counters)
+{
+    __shared__ int size_of[MMAX];
+    __shared__ int order[MMAX];                // scan position -> context id
+    __shared__ uint64_t cmask[MMAX][KWMAX];    // labels that the context at a scan position provides
+    __shared__ uint64_t Y[CH][KWMAX];          // Y_t
+    __shared__ uint64_t U[CH][KWMAX];          // still uncovered while scanning
+    __shared__ uint64_t S[CH];                 // S_t as a mask over scan positions
+    __shared__ int cnt[CH];
+    __shared__ int unc[CH];
+    __shared__ uint64_t prevY[KWMAX], prevProv[KWMAX];
+    __shared__ uint64_t prevS;
+    __shared__ int prevValid, total, total_unc;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int KW = (K + 63) / 64;
+
+    // contexts in scan order: size ascending, id ascending
+    if (tid < M) {
+        int s = 0;
+        for (int l = 0; l < K; ++l) s += member[(size_t)tid * K + l] ? 1 : 0;
+        size_of[tid] = s;
+    }
+    __syncthreads();
+    if (tid < M) {
+        int rank = 0;
+        for (int c = 0; c < M; ++c) rank += (size_of[c] < size_of[tid] || (size_of[c] == size_of[tid] && c < tid)) ? 1 : 0;
+        order[rank] = tid;
+    }
+    __syncthreads();
+    for (int w = wave; w < M * KW; w += 4) {
+        const int pos = w / KW, j = w % KW, c = order[pos], l = j * 64 + lane;
+        bool p = false;
+        if (l < K) p = member[(size_t)c * K + l] != 0 && (acc == nullptr || acc[(size_t)c * K + l] >= tau);
+        const uint64_t m = __ballot(p);
+        if (lane == 0) cmask[pos][j] = m;
+    }
+    if (tid == 0) {
+        total = 0; total_unc = 0; prevS = 0; prevValid = 0;
+        if (state && state->valid) {
+            prevValid = 1;
+            uint64_t pos_mask = 0;
+            for (int pos = 0; pos < M; ++pos)
+                if ((state->set_ids >> order[pos]) & 1ull) pos_mask |= 1ull << pos;
+            prevS = pos_mask;
+        }
+    }
+    if (tid < KW) prevY[tid] = (state && state->valid) ? state->labels[tid] : 0ull;
+    __syncthreads();
+    if (tid < KW) {
+        uint64_t pv = 0;
+        for (int pos = 0; pos < M; ++pos)
+            if ((prevS >> pos) & 1ull) pv |= cmask[pos][tid];
+        prevProv[tid] = pv;
+    }
+    if (tid == 0) row_offsets[0] = 0;
+    const bool sequential = state != nullptr || context_copy != 0;
+
+    for (int f0 = 0; f0 < F; f0 += CH) {
+        const int n = min(CH, F - f0);
+        __syncthreads();
+        // Y_t: one ballot per 64 labels
+        for (int w = wave; w < n * KW; w += 4) {
+            const int t = w / KW, j = w % KW, l = j * 64 + lane;
+            const bool a = l < K && scores[(size_t)(f0 + t) * K + l] >= theta;
+            const uint64_t m = __ballot(a);
+            if (lane == 0) { Y[t][j] = m; U[t][j] = m; }
+        }
+        __syncthreads();
+        // greedy cover, one frame per thread
+        if (tid < n) {
+            uint64_t sel = 0;
+            bool left = false;
+            for (int j = 0; j < KW; ++j) left |= U[tid][j] != 0;
+            for (int pos = 0; pos < M && left; ++pos) {
+                bool got = false;
+                for (int j = 0; j < KW; ++j) got |= (U[tid][j] & cmask[pos][j]) != 0;
+                if (got) {
+                    sel |= 1ull << pos;
+                    left = false;
+                    for (int j = 0; j < KW; ++j) { U[tid][j] &= ~cmask[pos][j]; left |= U[tid][j] != 0; }
+                }
+            }
+            S[tid] = sel;
+        }
+        __syncthreads();
+        // reuse branches of Alg. 2, in frame order
+        if (sequential && tid == 0) {
+            for (int t = 0; t < n; ++t) {
+                bool same = prevValid != 0, covered = prevValid != 0 && context_copy != 0;
+                for (int j = 0; j < KW; ++j) {
+                    same &= Y[t][j] == prevY[j];
+                    covered &= (Y[t][j] & ~prevProv[j]) == 0;
+                }
+                if (same || covered) {
+                    S[t] = prevS;
+                } else if (S[t] != prevS) {
+                    prevS = S[t];
+                    for (int j = 0; j < KW; ++j) {
+                        uint64_t pv = 0;
+                        for (int pos = 0; pos < M; ++pos)
+                            if ((prevS >> pos) & 1ull) pv |= cmask[pos][j];
+                        prevProv[j] = pv;
+                    }
+                }
+                for (int j = 0; j < KW; ++j) prevY[j] = Y[t][j];
+                prevValid = 1;
+            }
+        }
+        __syncthreads();
+        // sizes, uncovered labels
+        if (tid < n) {
+            const uint64_t sel = S[tid];
+            int u = 0;
+            for (int j = 0; j < KW; ++j) {
+                uint64_t pv = 0;
+                for (int pos = 0; pos < M; ++pos)
+                    if ((sel >> pos) & 1ull) pv |= cmask[pos][j];
+                u += __popcll(Y[tid][j] & ~pv);
+            }
+            cnt[tid] = __popcll(sel);
+            unc[tid] = u;
+        }
+        __syncthreads();
+        if (tid == 0) {  // exclusive scan of at most CH small counts
+            int run = total, ru = total_unc;
+            for (int t = 0; t < n; ++t) {
+                const int c = cnt[t];
+                cnt[t] = run;
+                run += c;
+                ru += unc[t];
+                row_offsets[f0 + t + 1] = run;
+            }
+            total = run; total_unc = ru;
+        }
+        __syncthreads();
+        if (tid < n) {
+            uint64_t sel = S[tid];
+            int o = cnt[tid];
+            while (sel) {
+                const int pos = __ffsll((unsigned long long)sel) - 1;
+                sel &= sel - 1;
+                if (o < cap) adapter_ids[o] = order[pos];
+                ++o;
+            }
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        counters[0] = total;
+        counters[1] = total_unc;
+        if (state && F > 0) {
+            uint64_t ids = 0;
+            for (int pos = 0; pos < M; ++pos)
+                if ((prevS >> pos) & 1ull) ids |= 1ull << order[pos];
+            state->valid = 1;
+            state->set_ids = ids;
+        }
+    }
+    if (state && F > 0 && tid < KW) state->labels[tid] = prevY[tid];
+}
+
+}  // namespace
+
+extern "C" size_t poly_select_state_bytes(int K)
+{
+    if (K <= 0) return 0;
+    return 16 + 8 * (size_t)((K + 63) / 64);
+}
+
+extern "C" int poly_select(const float *label_scores, int F, int K, const uint8_t *group_membership, int M,
+                           const poly_select_opts *opts, void *state, int32_t *row_offsets, int32_t *adapter_ids, int cap,
+                           int32_t *counters, void *stream)
+{
+    if (!opts || !group_membership || !row_offsets || !counters) return POLY_EINVAL;
+    if (F < 0 || K <= 0 || K > POLY_MAX_LABELS || M <= 0 || M > POLY_MAX_CONTEXTS || cap < 0) return POLY_EINVAL;
+    if ((F > 0 && !label_scores) || (cap > 0 && !adapter_ids)) return POLY_EINVAL;
+    hipLaunchKernelGGL(select_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, label_scores, F, K, group_membership, M, opts->theta,
+                       opts->context_copy, opts->acc, opts->tau, (SelState *)state, row_offsets, adapter_ids, cap, counters);
+    return hipGetLastError() == hipSuccess ? POLY_OK : POLY_EHIP;
+}

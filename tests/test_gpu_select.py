@@ -1,0 +1,91 @@
+"""poly_select on the GPU against the CPU checker: bit-exact CSR adapter sets."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2507_14959_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_select(scores, mem, cap=None, state=None, **kw):
+    dev = "cuda"
+    F, K = scores.shape
+    M = mem.shape[0]
+    cap = F * M if cap is None else cap
+    s = torch.from_numpy(np.ascontiguousarray(scores)).to(dev)
+    m = torch.from_numpy(np.ascontiguousarray(mem)).to(dev)
+    off = torch.full((F + 1,), -7, dtype=torch.int32, device=dev)
+    ids = torch.full((max(cap, 1),), -7, dtype=torch.int32, device=dev)
+    cnt = torch.full((2,), -7, dtype=torch.int32, device=dev)
+    acc = kw.pop("acc", None)
+    acc_t = torch.from_numpy(np.ascontiguousarray(acc)).to(dev) if acc is not None else None
+    binding.poly_select(s, m, off, ids[:cap] if cap else ids[:0], cnt, acc=acc_t, state=state, **kw)
+    torch.cuda.synchronize()
+    cnt = cnt.cpu().numpy()
+    return off.cpu().numpy(), ids.cpu().numpy()[:min(cap, cnt[0])], int(cnt[0]), int(cnt[1])
+
+
+def test_config4_stream_in_batches_of_64():
+    mem = synth.make_group_membership()
+    scores, _ = synth.make_label_stream(1024)
+    for a in range(0, 1024, 64):
+        off, ids, n, unc = gpu_select(scores[a:a + 64], mem)
+        o_off, o_ids, o_unc = oracle.select(scores[a:a + 64], mem)
+        assert np.array_equal(off, o_off) and np.array_equal(ids, o_ids) and n == len(o_ids) and unc == o_unc
+
+
+def test_whole_stream_in_one_call_spans_several_passes():
+    mem = synth.make_group_membership()
+    scores, _ = synth.make_label_stream(1000)          # 7 full passes of 128 frames + a ragged one
+    off, ids, n, unc = gpu_select(scores, mem)
+    o_off, o_ids, o_unc = oracle.select(scores, mem)
+    assert np.array_equal(off, o_off) and np.array_equal(ids, o_ids) and unc == o_unc
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("copy", [False, True])
+def test_overlapping_contexts_with_accuracy_table_and_state(seed, copy):
+    rng = np.random.default_rng(500 + seed)
+    K, M = [(12, 7), (80, 45), (200, 64), (64, 1), (65, 33), (1024, 64)][seed]
+    mem, acc = synth.make_cover_instance(seed, K, M, max_size=min(K, 6), with_acc=True)
+    T = 300
+    Y, cur = np.zeros((T, K), dtype=bool), np.zeros(K, dtype=bool)
+    for t in range(T):                                   # sticky stream so the reuse branches fire
+        if rng.random() < 0.4:
+            cur = np.zeros(K, dtype=bool)
+            cur[rng.choice(K, size=int(rng.integers(0, 4)), replace=False)] = True
+        Y[t] = cur
+    scores = np.where(Y, 0.9, 0.1).astype(np.float32)
+    o_state = oracle.SelectState(K, M)
+    g_state = torch.zeros(binding.poly_select_state_bytes(K), dtype=torch.uint8, device="cuda")
+    for a in range(0, T, 77):                            # state carried over ragged batches
+        o_off, o_ids, o_unc = oracle.select(scores[a:a + 77], mem, acc=acc, tau=0.3, context_copy=copy, state=o_state)
+        off, ids, n, unc = gpu_select(scores[a:a + 77], mem, acc=acc, tau=0.3, context_copy=copy, state=g_state)
+        assert np.array_equal(off, o_off), (seed, a)
+        assert np.array_equal(ids, o_ids) and unc == o_unc
+
+
+def test_threshold_is_inclusive_and_empty_frames_give_empty_sets():
+    mem = synth.make_group_membership(4, 5)
+    s = np.zeros((3, 20), dtype=np.float32)
+    s[0, 3] = 0.5; s[0, 7] = np.nextafter(np.float32(0.5), np.float32(0))   # exactly at / just under the threshold
+    s[2, 19] = 1.0
+    off, ids, n, unc = gpu_select(s, mem)
+    assert list(off) == [0, 1, 1, 2] and list(ids) == [0, 3] and unc == 0
+
+
+def test_small_cap_reports_needed_size_and_truncates():
+    mem = synth.make_group_membership()
+    scores, _ = synth.make_label_stream(64)
+    o_off, o_ids, _ = oracle.select(scores, mem)
+    off, ids, n, _ = gpu_select(scores, mem, cap=10)
+    assert n == len(o_ids) > 10 and np.array_equal(off, o_off) and np.array_equal(ids, o_ids[:10])
+
+
+def test_invalid_arguments_are_refused_on_the_host():
+    z = torch.zeros(4, dtype=torch.int32, device="cuda")
+    s = torch.zeros((1, 2000), device="cuda")
+    m = torch.zeros((2, 2000), dtype=torch.uint8, device="cuda")
+    assert binding.poly_select(s, m, z, z, z, check=False) == binding.POLY_EINVAL      # K above the limit

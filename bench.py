@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Throughput of the Polymorph hot path on one MI355X.
+
+One step = one pass of the whole path over one batch that is already resident in HBM:
+poly_select (label scores -> per-frame adapter sets, on the device) followed by poly_forward
+(patch embedding, 12 layers with per-row-block LoRA, heads, sigmoid, merge), with no host round
+trip in between.  Prints ONE JSON line: frames/s, the roofline of the dominant kernel (the bf16
+MFMA linear) from per-dispatch timings, and the CPU checker timed on the same batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def scores_for_sets(off, ids, n_groups=16, group_size=5):
+    """Label scores whose active labels make Alg. 2 select exactly the given adapter sets."""
+    F = len(off) - 1
+    s = np.full((F, n_groups * group_size), 0.05, dtype=np.float32)
+    for f in range(F):
+        for j, k in enumerate(ids[off[f]:off[f + 1]]):
+            s[f, k * group_size + (f + j) % group_size] = 0.95
+    return s
+
+
+def gemm_launches(cfg, F, R, L0):
+    """(rows, K, N, lora) of every linear launch of one forward, for the algorithmic flop count."""
+    T, D, Dm = cfg.T, cfg.D, cfg.Dm
+    out = [(F * (T - 1), cfg.patch_dim, D, False)]
+    for l in range(cfg.L):
+        if l >= L0 and R == 0:
+            break
+        ad = l >= L0
+        rows_qkv_in = (F if l <= L0 else R) * T      # the base product of the fan-out layer runs once per frame
+        rows = (R if ad else F) * T
+        out.append((rows_qkv_in, D, 3 * D, ad and cfg.targets & 1, rows))
+        out.append((rows, D, D, ad and cfg.targets & 2, rows))
+        out.append((rows, D, Dm, ad and cfg.targets & 4, rows))
+        out.append((rows, Dm, D, ad and cfg.targets & 8, rows))
+    return out
+
+
+def gemm_flops(cfg, F, R, L0):
+    total = 0.0
+    launches = gemm_launches(cfg, F, R, L0)
+    for item in launches:
+        rows, K, N, lora = item[:4]
+        total += 2.0 * rows * K * N
+        if lora:
+            total += 2.0 * item[4] * cfg.r * N     # expand (x A_k) B_k, fused into the same kernel
+    return total, len(launches)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--L0", type=int, default=0, help="first adapted layer (0 = all layers adapted; 10 = last 20 %%)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-checker baseline")
+    ap.add_argument("--no-extra", action="store_true", help="skip the side measurements (L0=10, isolated linear)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (frames shard trivially, see DESIGN.md); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2507_14959_amd import binding, synth
+
+    dev = "cuda"
+    cfg, w, frames_np, off_np, ids_np = synth.make_forward_case(2)
+    F, R = frames_np.shape[0], int(off_np[-1])
+    mem_np = synth.make_group_membership()
+    scores_np = scores_for_sets(off_np, ids_np)
+    K_labels = mem_np.shape[1]
+
+    def make_step(L0):
+        model = binding.DeviceModel(cfg, w, L0=L0)
+        frames = model.frames_to_device(frames_np)
+        scores = torch.from_numpy(scores_np).to(dev)
+        mem = torch.from_numpy(mem_np).to(dev)
+        cap = 3 * F
+        off = torch.zeros(F + 1, dtype=torch.int32, device=dev)
+        ids = torch.zeros(cap, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(2, dtype=torch.int32, device=dev)
+        st = torch.zeros(1, dtype=torch.int32, device=dev)
+        out = torch.zeros(cap, cfg.C, device=dev)
+        merged = torch.zeros(F, K_labels, device=dev)
+        ws = torch.empty(binding.poly_forward_workspace_bytes(model, F, cap), dtype=torch.uint8, device=dev)
+
+        def step():
+            binding.poly_select(scores, mem, off, ids, cnt)
+            binding.poly_forward(model, frames, off, ids, cap, out, ws, out_merged=merged, dev_status=st)
+        keep = (model, frames, scores, mem, off, ids, cnt, st, out, merged, ws)
+        return step, keep
+
+    def timed(step, steps, warmup):
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    step, keep = make_step(args.L0)
+    sec = timed(step, args.steps, args.warmup)
+
+    # the step really selected config 2's adapter sets and the device reported no error
+    off_d, ids_d, cnt_d, st_d = keep[4].cpu().numpy(), keep[5].cpu().numpy(), keep[6].cpu().numpy(), keep[7].cpu().numpy()
+    assert np.array_equal(off_d, off_np) and np.array_equal(ids_d[:R], ids_np) and int(st_d[0]) == 0 and int(cnt_d[0]) == R
+
+    # per-dispatch kernel times over a repeat of the timed steps
+    n_prof = min(args.steps, 50)
+    binding.poly_profile_begin(n_prof * 256)
+    for _ in range(n_prof):
+        step()
+    prof = binding.poly_profile_end()
+    flops, n_gemm = gemm_flops(cfg, F, R, args.L0)
+    g = prof["gemm"]
+    assert g["launches"] == n_gemm * n_prof, (g, n_gemm)
+    avg_ms = g["ms"] / g["launches"]
+    achieved = flops / n_gemm / (avg_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel (base linear + fused LoRA expand + epilogue)",
+                "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "launches_per_step": n_gemm, "avg_launch_us": round(avg_ms * 1e3, 2),
+                "algorithmic_gflop_per_launch": round(flops / n_gemm / 1e9, 3)}
+    stages = {k: {"launches_per_step": v["launches"] // n_prof, "us_per_step": round(v["ms"] * 1e3 / n_prof, 1)}
+              for k, v in prof.items()}
+
+    result = {
+        "metric": "frames/s, DeiT-tiny ~2 adapters/frame; multi-LoRA GEMM % of MFMA peak",
+        "value": round(F / sec, 1), "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"config 2: DeiT-tiny bf16 (fp32 accumulate), {F} frames 224x224, 16 adapters r=8 on qkv+proj, "
+                               f"1+Bin(2,0.4) adapters/frame (R={R} row-blocks, {R / F:.2f}/frame), L0={args.L0}; "
+                               "step = poly_select + poly_forward + merge",
+                   "frames": F, "row_blocks": R, "L0": args.L0},
+        "roofline": roofline,
+        "stages": stages,
+    }
+
+    if not args.no_extra:
+        extra = {}
+        # the paper's own placement: adapters on the final 20 % of the layers only
+        step10, keep10 = make_step(cfg.polymorph_L0())
+        sec10 = timed(step10, max(args.steps // 2, 10), 10)
+        extra["frames_per_s_L0_10"] = round(F / sec10, 1)
+        del step10, keep10
+        # isolated multi-LoRA linear (config 5): 256 x 197 x 768 -> 2304, 64 adapters r=16, 2 per block
+        case = synth.make_lora_linear_case()
+        elt = torch.bfloat16
+        up = lambda a, dt=elt: torch.from_numpy(np.ascontiguousarray(a)).to(device=dev, dtype=dt).contiguous()
+        X, Wt = up(case["X"]), up(case["W"].T)
+        At, Bt = up(np.swapaxes(case["A"], 1, 2)), up(np.swapaxes(case["B"], 1, 2))
+        bias = up(case["bias"], torch.float32)
+        o5, i5 = up(case["row_offsets"], torch.int32), up(case["adapter_ids"], torch.int32)
+        R5 = int(case["row_offsets"][-1])
+        Y = torch.empty(R5, 197, 2304, dtype=elt, device=dev)
+        ws5 = torch.empty(binding.poly_lora_linear_workspace_bytes(256, 197, 16, R5, 1), dtype=torch.uint8, device=dev)
+        run5 = lambda: binding.poly_lora_linear(X, Wt, bias, At, Bt, 1.0, o5, i5, R5, Y, ws5)
+        for _ in range(5):
+            run5()
+        torch.cuda.synchronize()
+        binding.poly_profile_begin(256)
+        for _ in range(20):
+            run5()
+        p5 = binding.poly_profile_end()
+        fl5 = 2.0 * 256 * 197 * 768 * 2304 + 2.0 * R5 * 197 * 16 * 2304        # base once per X block + expand
+        sh5 = 2.0 * R5 * 197 * 768 * 16
+        by5 = 2.0 * (256 * 197 * 768 + R5 * 197 * 2304 + 768 * 2304 + R5 * 197 * 16 + 64 * 16 * 2304)   # X, Y, W, S, Bt
+        g5 = p5["gemm"]["ms"] / p5["gemm"]["launches"] * 1e-3
+        s5 = p5["shrink"]["ms"] / p5["shrink"]["launches"] * 1e-3
+        extra["lora_linear_cfg5"] = {
+            "gemm_us": round(g5 * 1e6, 1), "gemm_tflops": round(fl5 / g5 / 1e12, 1), "gemm_frac_mfma": round(fl5 / g5 / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "gemm_GBs": round(by5 / g5 / 1e9, 1), "gemm_frac_hbm": round(by5 / g5 / 1e9 / PEAK_HBM_GBS, 4),
+            "shrink_us": round(s5 * 1e6, 1),
+            "shrink_GBs": round(2 * (R5 * 197 * 768 + R5 * 197 * 16) / s5 / 1e9, 1),
+            "shrink_gflops": round(sh5 / s5 / 1e9, 1)}
+        result["extra"] = extra
+
+    if not args.no_cpu:
+        import oracle
+        threads = int(oracle.lib().omp_get_max_threads())
+        t0 = time.perf_counter()
+        o_off, o_ids, _ = oracle.select(scores_np, mem_np)
+        want = oracle.forward(cfg, w, frames_np, o_off, o_ids, L0=args.L0, K=K_labels)
+        cpu_s = time.perf_counter() - t0
+        got = keep[8].cpu().numpy()[:R]
+        err = float(np.abs(got - want["scores"]).max())
+        result["cpu_baseline"] = {"value": round(F / cpu_s, 3), "unit": "frames/s", "cores": threads, "kind": "oracle",
+                                  "sample": f"one full step: the same {F}-frame batch ({R} row-blocks), select + forward, {cpu_s:.1f} s"}
+        result["max_abs_score_error_vs_oracle"] = err
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -189,6 +189,33 @@ int poly_lora_linear(const void *X, int n_xblocks, int T, int Kdim, const void *
                      const int32_t *row_offsets, const int32_t *adapter_ids, int R, void *Y, int dtype,
                      int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Per-stage kernel timing for measurement harnesses (not part of the method).  Between
+ * poly_profile_begin and poly_profile_end every kernel the library launches carries a start/stop
+ * event pair stamped by the runtime with the dispatch's own begin and end, and poly_profile_end
+ * (which synchronises the device) returns, per stage, the number of launches and the sum of their
+ * execution times in milliseconds.  `max_launches` bounds the number of recorded launches (host
+ * events are created for them); launches beyond it run untimed.  Process-wide, not thread-safe.
+ */
+enum {
+    POLY_STAGE_SELECT = 0, /* Alg. 2 kernel */
+    POLY_STAGE_GEMM = 1,   /* base linears with fused expand and epilogue (patch embedding included) */
+    POLY_STAGE_SHRINK = 2, /* x A_k */
+    POLY_STAGE_ATTN = 3,
+    POLY_STAGE_NORM = 4,   /* LayerNorm */
+    POLY_STAGE_OTHER = 5,  /* CSR check, patch gathering, class token, heads, merge */
+    POLY_STAGE_COUNT = 6
+};
+
+typedef struct poly_profile {
+    int32_t launches[POLY_STAGE_COUNT];
+    float ms[POLY_STAGE_COUNT];
+    int32_t dropped; /* recorded launches whose events could not be read */
+} poly_profile;
+
+int poly_profile_begin(int max_launches);
+int poly_profile_end(poly_profile *out); /* host struct */
+
 #ifdef __cplusplus
 }
 #endif

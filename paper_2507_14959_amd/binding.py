@@ -21,7 +21,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpoly.so")
 
 EXPORTS = ("poly_status_string", "poly_select_state_bytes", "poly_select", "poly_forward_workspace_bytes",
-           "poly_forward", "poly_lora_linear_workspace_bytes", "poly_lora_linear")
+           "poly_forward", "poly_lora_linear_workspace_bytes", "poly_lora_linear", "poly_profile_begin", "poly_profile_end")
+STAGES = ("select", "gemm", "shrink", "attention", "layernorm", "other")
 
 
 class ModelDesc(C.Structure):
@@ -46,6 +47,10 @@ class Heads(C.Structure):
 
 class SelectOpts(C.Structure):
     _fields_ = [("theta", C.c_float), ("context_copy", C.c_int32), ("acc", C.c_void_p), ("tau", C.c_float)]
+
+
+class Profile(C.Structure):
+    _fields_ = [("launches", C.c_int32 * 6), ("ms", C.c_float * 6), ("dropped", C.c_int32)]
 
 
 _lib = None
@@ -78,6 +83,10 @@ def lib():
         L.poly_lora_linear.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                        C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p, C.c_void_p,
                                        C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.poly_profile_begin.restype = C.c_int
+        L.poly_profile_begin.argtypes = [C.c_int]
+        L.poly_profile_end.restype = C.c_int
+        L.poly_profile_end.argtypes = [C.POINTER(Profile)]
         _lib = L
     return _lib
 
@@ -216,6 +225,21 @@ def poly_lora_linear(X: torch.Tensor, Wt: torch.Tensor, bias: Optional[torch.Ten
     if check and rc != POLY_OK:
         raise PolyError(rc, "poly_lora_linear")
     return rc
+
+
+def poly_profile_begin(max_launches: int) -> None:
+    rc = lib().poly_profile_begin(max_launches)
+    if rc != POLY_OK:
+        raise PolyError(rc, "poly_profile_begin")
+
+
+def poly_profile_end() -> Dict[str, Dict[str, float]]:
+    """Per-stage launch counts and summed kernel execution time (ms) since poly_profile_begin."""
+    p = Profile()
+    rc = lib().poly_profile_end(C.byref(p))
+    if rc != POLY_OK:
+        raise PolyError(rc, "poly_profile_end")
+    return {n: dict(launches=int(p.launches[i]), ms=float(p.ms[i])) for i, n in enumerate(STAGES)}
 
 
 # --------------------------------------------------------------------------- conveniences for tests and the bench

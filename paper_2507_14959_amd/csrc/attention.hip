@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *qkv, float *
 template <int NKT>
 void launch_bf16(const void *qkv, void *out, int T, int D, int heads, int n_blocks, const int *n_blocks_dev, hipStream_t st)
 {
-    hipLaunchKernelGGL(attn_bf16_kernel<NKT>, dim3((unsigned)(n_blocks * heads)), dim3(256), 0, st, (const bf16_t *)qkv, (bf16_t *)out, T, D,
+    POLY_LAUNCH(POLY_STAGE_ATTN, attn_bf16_kernel<NKT>, dim3((unsigned)(n_blocks * heads)), dim3(256), st, (const bf16_t *)qkv, (bf16_t *)out, T, D,
                        heads, n_blocks, n_blocks_dev);
 }
 
@@ -203,7 +203,7 @@ int launch_attention(const void *qkv, void *out, int T, int D, int heads, int n_
         default: return POLY_EINVAL;  // bf16 attention holds all keys of a block in 64 KB of LDS: T <= 224
         }
     } else {
-        hipLaunchKernelGGL(attn_f32_kernel, dim3((unsigned)(n_blocks * heads)), dim3(256), 0, st, (const float *)qkv, (float *)out, T, D, heads,
+        POLY_LAUNCH(POLY_STAGE_ATTN, attn_f32_kernel, dim3((unsigned)(n_blocks * heads)), dim3(256), st, (const float *)qkv, (float *)out, T, D, heads,
                            n_blocks, n_blocks_dev);
     }
     return hipGetLastError() == hipSuccess ? POLY_OK : POLY_EHIP;

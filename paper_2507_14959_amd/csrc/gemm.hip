@@ -264,15 +264,15 @@ int launch_gemm(const GemmArgs &g, int dtype, hipStream_t st)
         if (wide) {
             const long blocks = (long)g.n_in * tiles_m * ((g.N + 127) / 128);
             if (blocks > 0x7fffffffL) return POLY_EINVAL;
-            hipLaunchKernelGGL(gemm_bf16_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, st, g);
+            POLY_LAUNCH(POLY_STAGE_GEMM, gemm_bf16_kernel<128>, dim3((unsigned)blocks), dim3(256), st, g);
         } else {
             const long blocks = (long)g.n_in * tiles_m * ((g.N + 63) / 64);
-            hipLaunchKernelGGL(gemm_bf16_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, st, g);
+            POLY_LAUNCH(POLY_STAGE_GEMM, gemm_bf16_kernel<64>, dim3((unsigned)blocks), dim3(256), st, g);
         }
     } else {
         const long blocks = (long)g.n_in * ((g.T + 63) / 64) * ((g.N + 63) / 64);
         if (blocks > 0x7fffffffL) return POLY_EINVAL;
-        hipLaunchKernelGGL(gemm_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, g);
+        POLY_LAUNCH(POLY_STAGE_GEMM, gemm_f32_kernel, dim3((unsigned)blocks), dim3(256), st, g);
     }
     return hipGetLastError() == hipSuccess ? POLY_OK : POLY_EHIP;
 }

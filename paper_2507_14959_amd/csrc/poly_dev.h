@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/poly.h"
@@ -40,6 +41,18 @@ template <typename T> __device__ __forceinline__ float to_f32(T v) { return (flo
 template <typename T> __device__ __forceinline__ T from_f32(float v) { return (T)v; }
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
+
+// ---- launch with optional per-stage timing (profile.hip) ----
+bool poly_prof_next(int stage, hipEvent_t *a, hipEvent_t *b);
+
+#define POLY_LAUNCH(stage, kernel, grid, block, st, ...)                                         \
+    do {                                                                                         \
+        hipEvent_t ea_, eb_;                                                                     \
+        if (poly_prof_next(stage, &ea_, &eb_))                                                   \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, st, ea_, eb_, 0, __VA_ARGS__);         \
+        else                                                                                     \
+            hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);                         \
+    } while (0)
 
 // ---- stage launchers (defined in the .hip files, used by the entry points in api.hip) ----
 

@@ -211,7 +211,7 @@ static inline int hip_ok() { return hipGetLastError() == hipSuccess ? POLY_OK : 
 int launch_prep(const int32_t *row_offsets, const int32_t *adapter_ids, int F, int R_cap, int n_adapters, PolyMeta *meta,
                 int32_t *frame_of_row, int32_t *adapter_of_row, int32_t *dev_status, hipStream_t st)
 {
-    hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(256), 0, st, row_offsets, adapter_ids, F, R_cap, n_adapters, meta, frame_of_row,
+    POLY_LAUNCH(POLY_STAGE_OTHER, prep_kernel, dim3(1), dim3(256), st, row_offsets, adapter_ids, F, R_cap, n_adapters, meta, frame_of_row,
                        adapter_of_row, dev_status);
     return hip_ok();
 }
@@ -222,16 +222,16 @@ int launch_im2col(const void *frames, void *patches, int F, int H, int W, int p,
     if (total == 0) return POLY_OK;
     const unsigned blocks = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
     if (dtype == POLY_BF16)
-        hipLaunchKernelGGL(im2col_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t *)frames, (bf16_t *)patches, F, H, W, p);
+        POLY_LAUNCH(POLY_STAGE_OTHER, im2col_kernel<bf16_t>, dim3(blocks), dim3(256), st, (const bf16_t *)frames, (bf16_t *)patches, F, H, W, p);
     else
-        hipLaunchKernelGGL(im2col_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float *)frames, (float *)patches, F, H, W, p);
+        POLY_LAUNCH(POLY_STAGE_OTHER, im2col_kernel<float>, dim3(blocks), dim3(256), st, (const float *)frames, (float *)patches, F, H, W, p);
     return hip_ok();
 }
 
 int launch_cls(float *x, const float *cls, const float *pos, int F, int T, int D, hipStream_t st)
 {
     if (F == 0) return POLY_OK;
-    hipLaunchKernelGGL(cls_kernel, dim3((F * D + 255) / 256), dim3(256), 0, st, x, cls, pos, F, T, D);
+    POLY_LAUNCH(POLY_STAGE_OTHER, cls_kernel, dim3((F * D + 255) / 256), dim3(256), st, x, cls, pos, F, T, D);
     return hip_ok();
 }
 
@@ -242,9 +242,9 @@ int launch_layernorm(const float *x, void *y, const float *gain, const float *sh
     if (rows == 0) return POLY_OK;
     const unsigned blocks = (unsigned)((rows + 3) / 4);
     if (dtype == POLY_BF16)
-        hipLaunchKernelGGL(layernorm_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, x, (bf16_t *)y, gain, shift, D, eps, T, n_blocks, n_blocks_dev);
+        POLY_LAUNCH(POLY_STAGE_NORM, layernorm_kernel<bf16_t>, dim3(blocks), dim3(256), st, x, (bf16_t *)y, gain, shift, D, eps, T, n_blocks, n_blocks_dev);
     else
-        hipLaunchKernelGGL(layernorm_kernel<float>, dim3(blocks), dim3(256), 0, st, x, (float *)y, gain, shift, D, eps, T, n_blocks, n_blocks_dev);
+        POLY_LAUNCH(POLY_STAGE_NORM, layernorm_kernel<float>, dim3(blocks), dim3(256), st, x, (float *)y, gain, shift, D, eps, T, n_blocks, n_blocks_dev);
     return hip_ok();
 }
 
@@ -256,12 +256,12 @@ int launch_shrink(const void *X, int T, int K, const void *At, int r, int RP, fl
         if (K % 8 != 0) return POLY_EINVAL;
         const int subs = (T + 31) / 32;
         const unsigned blocks = (unsigned)(((size_t)n_out * subs + 3) / 4);
-        hipLaunchKernelGGL(shrink_bf16_kernel, dim3(blocks), dim3(256), 0, st, (const bf16_t *)X, T, K, (const bf16_t *)At, r, RP, scale, n_out,
+        POLY_LAUNCH(POLY_STAGE_SHRINK, shrink_bf16_kernel, dim3(blocks), dim3(256), st, (const bf16_t *)X, T, K, (const bf16_t *)At, r, RP, scale, n_out,
                            n_out_dev, in_block_of_out, adapter_of_out, (bf16_t *)S);
     } else {
         const size_t total = (size_t)n_out * T * RP;
         const unsigned blocks = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
-        hipLaunchKernelGGL(shrink_f32_kernel, dim3(blocks), dim3(256), 0, st, (const float *)X, T, K, (const float *)At, r, RP, scale, n_out,
+        POLY_LAUNCH(POLY_STAGE_SHRINK, shrink_f32_kernel, dim3(blocks), dim3(256), st, (const float *)X, T, K, (const float *)At, r, RP, scale, n_out,
                            n_out_dev, in_block_of_out, adapter_of_out, (float *)S);
     }
     return hip_ok();
@@ -273,10 +273,10 @@ int launch_head(const float *x, const int *src_block_of_row, int T, int D, const
 {
     if (R_cap == 0) return POLY_OK;
     if (dtype == POLY_BF16)
-        hipLaunchKernelGGL(head_kernel<bf16_t>, dim3(R_cap), dim3(64), 0, st, x, src_block_of_row, T, D, gain, shift, eps,
+        POLY_LAUNCH(POLY_STAGE_OTHER, head_kernel<bf16_t>, dim3(R_cap), dim3(64), st, x, src_block_of_row, T, D, gain, shift, eps,
                            (const bf16_t *)head_w, head_b, C, adapter_of_row, meta, logits, scores);
     else
-        hipLaunchKernelGGL(head_kernel<float>, dim3(R_cap), dim3(64), 0, st, x, src_block_of_row, T, D, gain, shift, eps,
+        POLY_LAUNCH(POLY_STAGE_OTHER, head_kernel<float>, dim3(R_cap), dim3(64), st, x, src_block_of_row, T, D, gain, shift, eps,
                            (const float *)head_w, head_b, C, adapter_of_row, meta, logits, scores);
     return hip_ok();
 }
@@ -286,9 +286,9 @@ int launch_merge(const float *scores, const int *frame_of_row, const int *adapte
 {
     const size_t n = (size_t)F * K;
     if (n == 0) return POLY_OK;
-    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((n + 255) / 256 > 4096 ? 4096 : (n + 255) / 256)), dim3(256), 0, st, merged, n);
+    POLY_LAUNCH(POLY_STAGE_OTHER, zero_kernel, dim3((unsigned)((n + 255) / 256 > 4096 ? 4096 : (n + 255) / 256)), dim3(256), st, merged, n);
     if (R_cap > 0)
-        hipLaunchKernelGGL(merge_kernel, dim3((R_cap * C + 255) / 256), dim3(256), 0, st, scores, frame_of_row, adapter_of_row, class_map,
+        POLY_LAUNCH(POLY_STAGE_OTHER, merge_kernel, dim3((R_cap * C + 255) / 256), dim3(256), st, scores, frame_of_row, adapter_of_row, class_map,
                            C, K, meta, merged);
     return hip_ok();
 }

@@ -200,7 +200,7 @@ extern "C" int poly_select(const float *label_scores, int F, int K, const uint8_
     if (!opts || !group_membership || !row_offsets || !counters) return POLY_EINVAL;
     if (F < 0 || K <= 0 || K > POLY_MAX_LABELS || M <= 0 || M > POLY_MAX_CONTEXTS || cap < 0) return POLY_EINVAL;
     if ((F > 0 && !label_scores) || (cap > 0 && !adapter_ids)) return POLY_EINVAL;
-    hipLaunchKernelGGL(select_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, label_scores, F, K, group_membership, M, opts->theta,
+    POLY_LAUNCH(POLY_STAGE_SELECT, select_kernel, dim3(1), dim3(256), (hipStream_t)stream, label_scores, F, K, group_membership, M, opts->theta,
                        opts->context_copy, opts->acc, opts->tau, (SelState *)state, row_offsets, adapter_ids, cap, counters);
     return hipGetLastError() == hipSuccess ? POLY_OK : POLY_EHIP;
 }

@@ -7,6 +7,8 @@
 // fp32: 64 x 64 x 16 tiles on the vector ALUs (reference-precision path).
 #include "poly_dev.h"
 
+#include <stdlib.h>
+
 namespace {
 
 template <typename T> __device__ __forceinline__ void epilogue_store_elt(const GemmArgs &g, int ob, int t, int col, float v)
@@ -28,10 +30,9 @@ template <typename T> __device__ __forceinline__ void epilogue_store_elt(const G
 }
 
 // decode the flat block index: n-tile fastest, then m-tile, then input block
-__device__ __forceinline__ bool decode_tile(const GemmArgs &g, int BM, int BN, int &xb, int &t0, int &n0, int &ob0, int &ob1)
+__device__ __forceinline__ bool decode_tile(const GemmArgs &g, int id, int BM, int BN, int &xb, int &t0, int &n0, int &ob0, int &ob1)
 {
     const int tiles_n = (g.N + BN - 1) / BN, tiles_m = (g.T + BM - 1) / BM;
-    int id = blockIdx.x;
     const int tn = id % tiles_n; id /= tiles_n;
     const int tm = id % tiles_m; xb = id / tiles_m;
     const int n_in = g.n_in_dev ? min(*g.n_in_dev, g.n_in) : g.n_in;
@@ -42,10 +43,10 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs &g, int BM, int BN, i
     return ob0 < ob1;
 }
 
-// ------------------------------------------------------------------ bf16 MFMA
+// ------------------------------------------------------------------ bf16 MFMA, any K % 8 == 0 and any N
 
 template <int BN>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g)
+__global__ __launch_bounds__(256) void gemm_bf16_generic_kernel(const GemmArgs g)
 {
     constexpr int BM = 128, BK = 32, LS = BK + 8;  // LDS row stride in elements (80 B, 16-byte aligned)
     constexpr int NJ = BN / 64;                     // 32-wide column subtiles per wave
@@ -53,9 +54,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g)
     __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LS];
 
     int xb, t0, n0, ob0, ob1;
-    if (!decode_tile(g, BM, BN, xb, t0, n0, ob0, ob1)) return;
+    if (!decode_tile(g, blockIdx.x, BM, BN, xb, t0, n0, ob0, ob1)) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1, lm = lane & 31, lh = lane >> 5;
     const bf16_t *A = (const bf16_t *)g.A + (size_t)xb * g.T * g.K;
     const bf16_t *Wt = (const bf16_t *)g.Wt;
@@ -187,6 +188,242 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g)
     }
 }
 
+// ------------------------------------------------------------------ bf16 MFMA, K % 64 == 0 and N % 8 == 0
+// 128 x BN x 64 tiles, 4 waves in a 2 x 2 grid, v_mfma_f32_32x32x16_bf16.
+//
+// Loads: global_load_lds_dwordx4 -- each wave instruction drops 64 x 16 bytes (8 tile rows of 64 elements)
+// straight into LDS, so NS - 1 k-tiles are in flight per workgroup without costing registers.  The lane that
+// fills position p of row r fetches chunk p ^ ((r >> 1) & 7): a swizzle that keeps 16-byte reads free of bank
+// conflicts for 8 or 16 lanes per LDS cycle, without padding.  Waits are counted by hand (vmcnt = loads of
+// the k-tiles still allowed in flight) and the barrier is a bare s_barrier, because a fenced barrier would
+// drain every outstanding load.
+//
+// The product is accumulated transposed (Wt fragment as the A operand) so that a lane ends up with four
+// consecutive output columns of one row; the epilogue adds the low-rank expand as one more MFMA K step per
+// 16 ranks, stages fp32 rows through LDS with 16-byte writes and stores whole 128/256-byte row segments,
+// adding bias, residual and position rows with vector loads.
+//
+// Tile order: workgroup ids are dealt round-robin to the 8 XCDs, so id % 8 picks the XCD.  Each XCD owns a
+// contiguous range of row tiles and walks it once per panel of PANEL column tiles, which keeps one W panel
+// and the row tiles in flight inside that XCD's 4 MB L2 instead of streaming all of W past every row tile.
+#define POLY_GLDS16(gptr, lptr)                                                                          \
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(gptr),           \
+                                     (void __attribute__((address_space(3))) *)(lptr), 16, 0, 0)
+
+template <int N> __device__ __forceinline__ void wait_vm_and_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+constexpr int GEMM_PANEL = 6;   // column tiles per panel
+
+// (row tile, column tile) of workgroup `bid`; false if this workgroup has nothing to do
+__device__ __forceinline__ bool xcd_tile(int bid, int tiles_mtot, int tiles_n, int &mt, int &tn)
+{
+    const int xcd = bid & 7, j = bid >> 3;
+    const int per = (tiles_mtot + 7) >> 3;                 // row tiles per XCD
+    const int m_lo = xcd * per, m_cnt = min(per, tiles_mtot - m_lo);
+    if (m_cnt <= 0) return false;
+    const int full = m_cnt * GEMM_PANEL;                   // workgroups per full panel
+    const int pn = j / full, rem = j - pn * full;
+    const int n_lo = pn * GEMM_PANEL;
+    if (n_lo >= tiles_n) return false;
+    const int width = min(GEMM_PANEL, tiles_n - n_lo);
+    const int ml = rem / width;
+    if (ml >= m_cnt) return false;
+    mt = m_lo + ml;
+    tn = n_lo + rem - ml * width;
+    return true;
+}
+
+template <int BN, int NS>
+__global__ __launch_bounds__(256, 2) void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
+{
+    constexpr int BM = 128, BK = 64;
+    constexpr int NJ = BN / 64;                 // 32-wide column subtiles per wave
+    constexpr int A_EL = BM * BK, B_EL = BN * BK, STAGE_EL = A_EL + B_EL;
+    constexpr int NC = BN / 8;                  // 16-byte chunks per staged fp32 row of a wave tile (BN/2 columns)
+    constexpr int AG = BM / 32, BG = BN / 32;   // 8-row groups (1 KB each) per wave and stage
+    constexpr int NLD = AG + BG;                // loads per wave and stage
+    extern __shared__ __attribute__((aligned(16))) bf16_t dsmem[];
+
+    int mt, tn;
+    if (!xcd_tile(blockIdx.x, g.n_in * tiles_m, tiles_n, mt, tn)) return;
+    const int xb = mt / tiles_m, t0 = (mt - xb * tiles_m) * BM, n0 = tn * BN;
+    const int n_in = g.n_in_dev ? min(*g.n_in_dev, g.n_in) : g.n_in;
+    if (xb >= n_in) return;
+    int ob0 = xb, ob1 = xb + 1;
+    if (g.out_off) { ob0 = g.out_off[xb]; ob1 = g.out_off[xb + 1]; }
+    if (ob0 >= ob1) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1, lm = lane & 31, lh = lane >> 5;
+    const bf16_t *A = (const bf16_t *)g.A + (size_t)xb * g.T * g.K;
+    const bf16_t *Wt = (const bf16_t *)g.Wt;
+
+    // rows past the end of the block / of W are clamped: their products land in accumulator rows / columns that
+    // are never stored
+    const int lr = lane >> 3;   // row inside an 8-row group; lane & 7 = position inside the row
+    int ga[AG], gb[BG];
+#pragma unroll
+    for (int i = 0; i < AG; ++i) {
+        const int row = (wave * AG + i) * 8 + lr;          // (row >> 1) & 7 = ((i & 1) << 2) | (lr >> 1)
+        ga[i] = min(t0 + row, g.T - 1) * g.K + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+    }
+#pragma unroll
+    for (int i = 0; i < BG; ++i) {
+        const int row = (wave * BG + i) * 8 + lr;
+        gb[i] = min(n0 + row, g.N - 1) * g.K + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+    }
+    auto issue = [&](int kt, int s) {
+        bf16_t *st = dsmem + s * STAGE_EL;
+#pragma unroll
+        for (int i = 0; i < AG; ++i) POLY_GLDS16(A + ga[i] + kt * BK, st + (wave * AG + i) * 512);
+#pragma unroll
+        for (int i = 0; i < BG; ++i) POLY_GLDS16(Wt + gb[i] + kt * BK, st + A_EL + (wave * BG + i) * 512);
+    };
+
+    f32x16 acc[2][NJ];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // fragment rows are wm*64 + i*32 + lm and wn*BN/2 + j*32 + lm: (row >> 1) & 7 == (lm >> 1) & 7 for all of them
+    const int fa0 = (wm * 64 + lm) * BK, fb0 = A_EL + (wn * (BN / 2) + lm) * BK, sw = (lm >> 1) & 7;
+    const int nk = g.K / BK;
+    const int npro = min(NS, nk);
+    for (int s = 0; s < npro; ++s) issue(s, s);
+    for (int it = 0; it < nk; ++it) {
+        // k-tiles issued beyond `it` may stay in flight; everything up to `it` must have landed
+        const int last_issued = it == 0 ? npro - 1 : min(nk - 1, it + NS - 2);
+        const int ahead = last_issued - it;
+        if (NS >= 4 && ahead >= 3) wait_vm_and_barrier<3 * NLD>();
+        else if (NS >= 3 && ahead == 2) wait_vm_and_barrier<2 * NLD>();
+        else if (ahead == 1) wait_vm_and_barrier<NLD>();
+        else wait_vm_and_barrier<0>();
+        // every wave is past compute(it - 1): its stage can be refilled
+        if (it >= 1 && it + NS - 1 < nk) issue(it + NS - 1, (it - 1) % NS);
+        const bf16_t *cur = dsmem + (it % NS) * STAGE_EL;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int ko = ((2 * kk + lh) ^ sw) << 3;
+            bf16x8 fa[2], fb[NJ];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) fa[i] = *(const bf16x8 *)(cur + fa0 + i * 32 * BK + ko);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) fb[j] = *(const bf16x8 *)(cur + fb0 + j * 32 * BK + ko);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        }
+    }
+    __syncthreads();   // all loads have landed (vmcnt(0) above) and all waves are done with the tiles
+
+    // ---- epilogue.  acc[i][j][e] = C[row wm*64 + i*32 + lm][col wn*BN/2 + j*32 + 8*(e/4) + 4*lh + e%4]
+    // staging tile of this wave: 64 rows x NC chunks of 4 floats; chunk ch of row r sits at ch ^ swz(r)
+    float *stg = (float *)dsmem + wave * (64 * NC * 4);
+    auto swz = [](int r) { return NC == 16 ? (r & 15) : ((r >> 1) & 7); };
+    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    const bool single = ob0 + 1 == ob1;
+    bool live[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) live[i] = t0 + wm * 64 + i * 32 < g.T;
+
+    // read-back mapping: NC consecutive lanes cover one row segment; each pass covers 64 / NC rows
+    constexpr int RPP = 64 / NC;
+    const int rch = lane % NC, rrow = lane / NC;
+    const int col = n0 + wn * (BN / 2) + rch * 4;
+    const bool col_ok = col < g.N;
+    f32x4 bias4 = {0.f, 0.f, 0.f, 0.f};
+    if (g.bias && col_ok) bias4 = *(const f32x4 *)(g.bias + col);
+
+    for (int ob = ob0; ob < ob1; ++ob) {
+        const int k_ad = (g.S && g.adapter_of_out) ? g.adapter_of_out[ob] : -1;
+        // registers (+ low-rank expand) -> LDS, one 32-row subtile at a time so that a second copy of the
+        // accumulators is only ever 16 * NJ registers
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            if (!live[i]) continue;
+            f32x16 c[NJ];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) c[j] = acc[i][j];
+            if (k_ad >= 0) {
+                const int t = t0 + wm * 64 + i * 32 + lm;
+                const bf16_t *S = (const bf16_t *)g.S + ((size_t)ob * g.T + min(t, g.T - 1)) * g.RP;
+                const bf16_t *Bt = (const bf16_t *)g.Bt + (size_t)k_ad * g.N * g.r;
+                for (int s0 = 0; s0 < g.RP; s0 += 16) {
+                    const int j0 = s0 + lh * 8;
+                    const bf16x8 fs = *(const bf16x8 *)(S + j0);    // rows past T feed rows that are never stored
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        const int bcol = n0 + wn * (BN / 2) + j * 32 + lm;
+                        bf16x8 f = zero8;
+                        if (bcol < g.N) {
+                            const bf16_t *p = Bt + (size_t)bcol * g.r + j0;
+                            if ((g.r & 7) == 0) {
+                                if (j0 + 8 <= g.r) f = *(const bf16x8 *)p;
+                            } else {
+#pragma unroll
+                                for (int q = 0; q < 8; ++q)
+                                    if (j0 + q < g.r) f[q] = p[q];
+                            }
+                        }
+                        c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, fs, c[j], 0, 0, 0);
+                    }
+                }
+            }
+            const int srow = i * 32 + lm;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int ch = j * 8 + 2 * q + lh;
+                    const f32x4 v = {c[j][4 * q], c[j][4 * q + 1], c[j][4 * q + 2], c[j][4 * q + 3]};
+                    *(f32x4 *)(stg + srow * (NC * 4) + ((ch ^ swz(srow)) << 2)) = v;
+                }
+        }
+        __syncthreads();
+        // LDS -> global
+        const int rows_left = g.T - (t0 + wm * 64);     // rows of this wave tile inside the block
+        const size_t obase = ((size_t)ob * g.Tout + g.t_off + t0 + wm * 64) * g.N + col;
+        if (g.mode == EPI_RESID) {
+            const int rb = g.res ? (g.res_block_of_out ? g.res_block_of_out[ob] : ob) : 0;
+            const float *res = g.res ? g.res + ((size_t)rb * g.Tout + g.t_off + t0 + wm * 64) * g.N + col : nullptr;
+            const float *pos = g.pos ? g.pos + (size_t)(g.t_off + t0 + wm * 64) * g.N + col : nullptr;
+            float *out = (float *)g.out + obase;
+#pragma unroll 4
+            for (int q = 0; q < NC; ++q) {
+                const int row = q * RPP + rrow;
+                if (row >= rows_left || !col_ok) continue;
+                f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4;
+                if (res) v += *(const f32x4 *)(res + (size_t)row * g.N);
+                if (pos) v += *(const f32x4 *)(pos + (size_t)row * g.N);
+                *(f32x4 *)(out + (size_t)row * g.N) = v;
+            }
+        } else {
+            bf16_t *out = (bf16_t *)g.out + obase;
+            const bool gelu = g.mode == EPI_GELU;
+#pragma unroll 4
+            for (int q = 0; q < NC; ++q) {
+                const int row = q * RPP + rrow;
+                if (row >= rows_left || !col_ok) continue;
+                f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4;
+                if (gelu) {
+#pragma unroll
+                    for (int z = 0; z < 4; ++z) v[z] = gelu_erf(v[z]);
+                }
+                const bf16x4 w = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+                *(bf16x4 *)(out + (size_t)row * g.N) = w;
+            }
+        }
+        if (!single) __syncthreads();   // the staging tile is rewritten by the next output block
+    }
+}
+
 // ------------------------------------------------------------------ fp32 vector ALU
 
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g)
@@ -196,7 +433,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g)
     __shared__ float Bs[BK][BN + 4];
 
     int xb, t0, n0, ob0, ob1;
-    if (!decode_tile(g, BM, BN, xb, t0, n0, ob0, ob1)) return;
+    if (!decode_tile(g, blockIdx.x, BM, BN, xb, t0, n0, ob0, ob1)) return;
 
     const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
     const float *A = (const float *)g.A + (size_t)xb * g.T * g.K;
@@ -253,21 +490,49 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g)
 
 }  // namespace
 
+// grid of the XCD-panel order: every XCD gets ceil(row tiles / 8) row tiles x all column tiles
+static unsigned dma_grid(int tiles_mtot, int tiles_n)
+{
+    const long per = (tiles_mtot + 7) / 8;
+    return (unsigned)(per * tiles_n * 8);
+}
+
 int launch_gemm(const GemmArgs &g, int dtype, hipStream_t st)
 {
     if (g.n_in <= 0 || g.T <= 0) return POLY_OK;
     if (dtype == POLY_BF16) {
         if (g.K % 8 != 0 || (g.S && g.RP % 16 != 0)) return POLY_EINVAL;
         const int tiles_m = (g.T + 127) / 128;
-        // wide outputs take 128-column tiles; narrow ones 64 so that small batches still fill the CUs
-        const bool wide = g.N >= 1024 || (long)g.n_in * tiles_m * ((g.N + 127) / 128) >= 1024;
-        if (wide) {
-            const long blocks = (long)g.n_in * tiles_m * ((g.N + 127) / 128);
-            if (blocks > 0x7fffffffL) return POLY_EINVAL;
-            POLY_LAUNCH(POLY_STAGE_GEMM, gemm_bf16_kernel<128>, dim3((unsigned)blocks), dim3(256), st, g);
+        // 128-column tiles when they divide N or N is large; 64-column tiles otherwise (no wasted columns at
+        // N = 192 or 576, and more workgroups for small batches)
+        const bool wide = g.N % 128 == 0 || g.N >= 1024;
+        const int tiles_n = wide ? (g.N + 127) / 128 : (g.N + 63) / 64;
+        const long blocks = (long)g.n_in * tiles_m * tiles_n;
+        if (blocks > 0x3fffffffL || (long)g.N * g.K > 0x7fffffffL || (long)g.T * g.K > 0x7fffffffL) return POLY_EINVAL;
+        if (g.K % 64 == 0 && g.N % 8 == 0) {
+            static const int variant = getenv("POLY_GEMM_VARIANT") ? atoi(getenv("POLY_GEMM_VARIANT")) : 1;
+            const unsigned grid = dma_grid(g.n_in * tiles_m, tiles_n);
+            if (variant == 1) {
+                if (wide)
+                    POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, (gemm_bf16_dma_kernel<128, 2>), dim3(grid), dim3(256), 2 * (128 + 128) * 64 * 2, st, g, tiles_m, tiles_n);
+                else
+                    POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, (gemm_bf16_dma_kernel<64, 2>), dim3(grid), dim3(256), 2 * (128 + 64) * 64 * 2, st, g, tiles_m, tiles_n);
+            } else {
+                static bool attr_set = false;
+                if (!attr_set) {
+                    (void)hipFuncSetAttribute((const void *)gemm_bf16_dma_kernel<128, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * (128 + 128) * 64 * 2);
+                    (void)hipFuncSetAttribute((const void *)gemm_bf16_dma_kernel<64, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * (128 + 64) * 64 * 2);
+                    attr_set = true;
+                }
+                if (wide)
+                    POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, (gemm_bf16_dma_kernel<128, 3>), dim3(grid), dim3(256), 3 * (128 + 128) * 64 * 2, st, g, tiles_m, tiles_n);
+                else
+                    POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, (gemm_bf16_dma_kernel<64, 3>), dim3(grid), dim3(256), 3 * (128 + 64) * 64 * 2, st, g, tiles_m, tiles_n);
+            }
+        } else if (wide) {
+            POLY_LAUNCH(POLY_STAGE_GEMM, gemm_bf16_generic_kernel<128>, dim3((unsigned)blocks), dim3(256), st, g);
         } else {
-            const long blocks = (long)g.n_in * tiles_m * ((g.N + 63) / 64);
-            POLY_LAUNCH(POLY_STAGE_GEMM, gemm_bf16_kernel<64>, dim3((unsigned)blocks), dim3(256), st, g);
+            POLY_LAUNCH(POLY_STAGE_GEMM, gemm_bf16_generic_kernel<64>, dim3((unsigned)blocks), dim3(256), st, g);
         }
     } else {
         const long blocks = (long)g.n_in * ((g.T + 63) / 64) * ((g.N + 63) / 64);

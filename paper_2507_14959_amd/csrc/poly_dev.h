@@ -54,6 +54,15 @@ bool poly_prof_next(int stage, hipEvent_t *a, hipEvent_t *b);
             hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);                         \
     } while (0)
 
+#define POLY_LAUNCH_SHMEM(stage, kernel, grid, block, shmem, st, ...)                            \
+    do {                                                                                         \
+        hipEvent_t ea_, eb_;                                                                     \
+        if (poly_prof_next(stage, &ea_, &eb_))                                                   \
+            hipExtLaunchKernelGGL(kernel, grid, block, shmem, st, ea_, eb_, 0, __VA_ARGS__);     \
+        else                                                                                     \
+            hipLaunchKernelGGL(kernel, grid, block, shmem, st, __VA_ARGS__);                     \
+    } while (0)
+
 // ---- stage launchers (defined in the .hip files, used by the entry points in api.hip) ----
 
 enum { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2 };

@@ -151,39 +151,67 @@ extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *b
         };
         auto use = [&](int t) { return lora_on && (m->targets & (1 << t)); };
 
+        // narrow models (D <= 192, bf16): LayerNorm, shrink, base product and expand of one linear run in one
+        // kernel that keeps 64 token rows on chip; otherwise LayerNorm / shrink / GEMM are separate launches
+        auto fused = [&](int t) { return dt == POLY_BF16 && rowlin_supported(D, t == 0 ? 3 * D : (t == 2 ? Dm : D), m->r, use(t)); };
+        auto rowlin = [&](int t, const float *x_ln, const float *ln_g, const float *ln_b, const void *a_in, const int *in_map,
+                          const void *Wt, const float *bias, int N, int mode, void *out, const float *res, const int *res_map) -> int {
+            RowLinArgs a = {};
+            a.x_ln = x_ln; a.ln_g = ln_g; a.ln_b = ln_b; a.eps = m->ln_eps; a.a_in = (const bf16_t *)a_in; a.in_block_of_out = in_map;
+            a.T = T; a.K = D; a.N = N; a.n_out = n_out; a.n_out_dev = n_out_dev;
+            a.Wt = (const bf16_t *)Wt; a.bias = bias;
+            if (use(t)) {
+                a.At = (const bf16_t *)lora_ptr(lora->At[t], t, D, N, true); a.Bt = (const bf16_t *)lora_ptr(lora->Bt[t], t, D, N, false);
+                a.r = m->r; a.scale = m->lora_scale; a.adapter_of_out = w.adapter_of_row;
+            }
+            a.mode = mode; a.out = out; a.res = res; a.res_block_of_out = res_map;
+            return launch_rowlin(a, st);
+        };
+        const int *fan_map = fan ? w.frame_of_row : nullptr;
+        const void *Wqkv = (const char *)base->qkv_w + es * (size_t)l * 3 * D * D, *Wproj = (const char *)base->proj_w + es * (size_t)l * D * D;
+        const void *Wfc1 = (const char *)base->fc1_w + es * (size_t)l * Dm * D;
+
         // ---- attention half
-        POLY_TRY(launch_layernorm(x_in, w.u, base->ln1_g + (size_t)l * D, base->ln1_b + (size_t)l * D, D, m->ln_eps, T, nb, nb_dev, dt, st));
-        {
+        if (fused(0)) {
+            POLY_TRY(rowlin(0, x_in, base->ln1_g + (size_t)l * D, base->ln1_b + (size_t)l * D, nullptr, fan_map, Wqkv,
+                            base->qkv_b + (size_t)l * 3 * D, 3 * D, EPI_STORE, w.qkv, nullptr, nullptr));
+        } else {
+            POLY_TRY(launch_layernorm(x_in, w.u, base->ln1_g + (size_t)l * D, base->ln1_b + (size_t)l * D, D, m->ln_eps, T, nb, nb_dev, dt, st));
             GemmArgs g = {};
-            g.A = w.u; g.Wt = (const char *)base->qkv_w + es * (size_t)l * 3 * D * D; g.bias = base->qkv_b + (size_t)l * 3 * D;
+            g.A = w.u; g.Wt = Wqkv; g.bias = base->qkv_b + (size_t)l * 3 * D;
             g.T = T; g.K = D; g.N = 3 * D; g.n_in = nb; g.n_in_dev = fan ? &w.meta->F_ok : nb_dev;
             g.out_off = fan ? row_offsets : nullptr;
             if (use(0)) {
                 const void *At = lora_ptr(lora->At[0], 0, D, 3 * D, true), *Bt = lora_ptr(lora->Bt[0], 0, D, 3 * D, false);
-                POLY_TRY(launch_shrink(w.u, T, D, At, m->r, RP, m->lora_scale, R, R_dev, fan ? w.frame_of_row : nullptr, w.adapter_of_row, w.S, dt, st));
+                POLY_TRY(launch_shrink(w.u, T, D, At, m->r, RP, m->lora_scale, R, R_dev, fan_map, w.adapter_of_row, w.S, dt, st));
                 g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = m->r; g.adapter_of_out = w.adapter_of_row;
             }
             g.mode = EPI_STORE; g.out = w.qkv; g.Tout = T;
             POLY_TRY(launch_gemm(g, dt, st));
         }
         POLY_TRY(launch_attention(w.qkv, w.o, T, D, m->heads, n_out, n_out_dev, dt, st));
-        {
+        if (fused(1)) {
+            POLY_TRY(rowlin(1, nullptr, nullptr, nullptr, w.o, nullptr, Wproj, base->proj_b + (size_t)l * D, D, EPI_RESID, x_out, x_in, fan_map));
+        } else {
             GemmArgs g = {};
-            g.A = w.o; g.Wt = (const char *)base->proj_w + es * (size_t)l * D * D; g.bias = base->proj_b + (size_t)l * D;
+            g.A = w.o; g.Wt = Wproj; g.bias = base->proj_b + (size_t)l * D;
             g.T = T; g.K = D; g.N = D; g.n_in = n_out; g.n_in_dev = n_out_dev;
             if (use(1)) {
                 const void *At = lora_ptr(lora->At[1], 1, D, D, true), *Bt = lora_ptr(lora->Bt[1], 1, D, D, false);
                 POLY_TRY(launch_shrink(w.o, T, D, At, m->r, RP, m->lora_scale, R, R_dev, nullptr, w.adapter_of_row, w.S, dt, st));
                 g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = m->r; g.adapter_of_out = w.adapter_of_row;
             }
-            g.mode = EPI_RESID; g.out = x_out; g.Tout = T; g.res = x_in; g.res_block_of_out = fan ? w.frame_of_row : nullptr;
+            g.mode = EPI_RESID; g.out = x_out; g.Tout = T; g.res = x_in; g.res_block_of_out = fan_map;
             POLY_TRY(launch_gemm(g, dt, st));
         }
         // ---- MLP half (x_out holds the stream from here on)
-        POLY_TRY(launch_layernorm(x_out, w.u, base->ln2_g + (size_t)l * D, base->ln2_b + (size_t)l * D, D, m->ln_eps, T, n_out, n_out_dev, dt, st));
-        {
+        if (fused(2)) {
+            POLY_TRY(rowlin(2, x_out, base->ln2_g + (size_t)l * D, base->ln2_b + (size_t)l * D, nullptr, nullptr, Wfc1,
+                            base->fc1_b + (size_t)l * Dm, Dm, EPI_GELU, w.h, nullptr, nullptr));
+        } else {
+            POLY_TRY(launch_layernorm(x_out, w.u, base->ln2_g + (size_t)l * D, base->ln2_b + (size_t)l * D, D, m->ln_eps, T, n_out, n_out_dev, dt, st));
             GemmArgs g = {};
-            g.A = w.u; g.Wt = (const char *)base->fc1_w + es * (size_t)l * Dm * D; g.bias = base->fc1_b + (size_t)l * Dm;
+            g.A = w.u; g.Wt = Wfc1; g.bias = base->fc1_b + (size_t)l * Dm;
             g.T = T; g.K = D; g.N = Dm; g.n_in = n_out; g.n_in_dev = n_out_dev;
             if (use(2)) {
                 const void *At = lora_ptr(lora->At[2], 2, D, Dm, true), *Bt = lora_ptr(lora->Bt[2], 2, D, Dm, false);

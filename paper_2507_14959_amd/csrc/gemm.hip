@@ -215,20 +215,18 @@ template <int N> __device__ __forceinline__ void wait_vm_and_barrier()
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-constexpr int GEMM_PANEL = 6;   // column tiles per panel
-
 // (row tile, column tile) of workgroup `bid`; false if this workgroup has nothing to do
-__device__ __forceinline__ bool xcd_tile(int bid, int tiles_mtot, int tiles_n, int &mt, int &tn)
+__device__ __forceinline__ bool xcd_tile(int bid, int tiles_mtot, int tiles_n, int panel, int &mt, int &tn)
 {
     const int xcd = bid & 7, j = bid >> 3;
     const int per = (tiles_mtot + 7) >> 3;                 // row tiles per XCD
     const int m_lo = xcd * per, m_cnt = min(per, tiles_mtot - m_lo);
     if (m_cnt <= 0) return false;
-    const int full = m_cnt * GEMM_PANEL;                   // workgroups per full panel
+    const int full = m_cnt * panel;                        // workgroups per full panel
     const int pn = j / full, rem = j - pn * full;
-    const int n_lo = pn * GEMM_PANEL;
+    const int n_lo = pn * panel;
     if (n_lo >= tiles_n) return false;
-    const int width = min(GEMM_PANEL, tiles_n - n_lo);
+    const int width = min(panel, tiles_n - n_lo);
     const int ml = rem / width;
     if (ml >= m_cnt) return false;
     mt = m_lo + ml;
@@ -236,28 +234,28 @@ __device__ __forceinline__ bool xcd_tile(int bid, int tiles_mtot, int tiles_n, i
     return true;
 }
 
-template <int BN, int NS>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
+// BM x BN tile, WM x WN waves, each wave (BM/WM) x (BN/WN) = (MI*32) x (NJ*32); NS LDS stages of 64 k-columns
+template <int BM, int BN, int WM, int WN, int NS>
+__global__ __launch_bounds__(64 * WM * WN, (BM * BN >= 256 * 256 || NS * (BM + BN) * 128 > 80 * 1024) ? 1 : 2)
+void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
 {
-    constexpr int BM = 128, BK = 64;
-    constexpr int NJ = BN / 64;                 // 32-wide column subtiles per wave
+    constexpr int BK = 64, NW = WM * WN;
+    constexpr int MI = BM / WM / 32, NJ = BN / WN / 32;   // 32 x 32 subtiles per wave
     constexpr int A_EL = BM * BK, B_EL = BN * BK, STAGE_EL = A_EL + B_EL;
-    constexpr int NC = BN / 8;                  // 16-byte chunks per staged fp32 row of a wave tile (BN/2 columns)
-    constexpr int AG = BM / 32, BG = BN / 32;   // 8-row groups (1 KB each) per wave and stage
-    constexpr int NLD = AG + BG;                // loads per wave and stage
+    constexpr int NC = NJ * 8;                             // 16-byte chunks per staged fp32 row (NJ*32 columns)
+    constexpr int AG = BM / 8 / NW, BG = BN / 8 / NW;      // 8-row groups (1 KB each) per wave and stage
+    constexpr int NLD = AG + BG;                           // loads per wave and stage
+    constexpr int PANEL = 768 / BN;                        // column tiles per L2 panel (1.2 MB of W at K = 768)
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && (NS - 1) * NLD <= 63, "tile / wave layout");
+    static_assert(NW * 32 * NC * 16 <= NS * STAGE_EL * 2, "staging must fit in the tile ring");
     extern __shared__ __attribute__((aligned(16))) bf16_t dsmem[];
 
     int mt, tn;
-    if (!xcd_tile(blockIdx.x, g.n_in * tiles_m, tiles_n, mt, tn)) return;
+    if (!xcd_tile(blockIdx.x, g.n_in * tiles_m, tiles_n, PANEL, mt, tn)) return;
     const int xb = mt / tiles_m, t0 = (mt - xb * tiles_m) * BM, n0 = tn * BN;
-    const int n_in = g.n_in_dev ? min(*g.n_in_dev, g.n_in) : g.n_in;
-    if (xb >= n_in) return;
-    int ob0 = xb, ob1 = xb + 1;
-    if (g.out_off) { ob0 = g.out_off[xb]; ob1 = g.out_off[xb + 1]; }
-    if (ob0 >= ob1) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1, lm = lane & 31, lh = lane >> 5;
+    const int wm = wave / WN, wn = wave % WN, lm = lane & 31, lh = lane >> 5;
     const bf16_t *A = (const bf16_t *)g.A + (size_t)xb * g.T * g.K;
     const bf16_t *Wt = (const bf16_t *)g.Wt;
 
@@ -267,7 +265,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_dma_kernel(const GemmArgs g,
     int ga[AG], gb[BG];
 #pragma unroll
     for (int i = 0; i < AG; ++i) {
-        const int row = (wave * AG + i) * 8 + lr;          // (row >> 1) & 7 = ((i & 1) << 2) | (lr >> 1)
+        const int row = (wave * AG + i) * 8 + lr;
         ga[i] = min(t0 + row, g.T - 1) * g.K + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
     }
 #pragma unroll
@@ -283,25 +281,79 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_dma_kernel(const GemmArgs g,
         for (int i = 0; i < BG; ++i) POLY_GLDS16(Wt + gb[i] + kt * BK, st + A_EL + (wave * BG + i) * 512);
     };
 
-    f32x16 acc[2][NJ];
+    // The tile loads need nothing but the tile coordinates, so they go out first; the row count, the fan-out
+    // offsets and the adapter id are read while they fly.  A tile that turns out to be past the true row count
+    // still read inside the caller's buffers (sized for the row bound); it drains its loads and leaves.
+    const int nk = g.K / BK;
+    const int npro = min(NS, nk);
+    for (int s = 0; s < npro; ++s) issue(s, s);
+    const int n_in = g.n_in_dev ? min(*g.n_in_dev, g.n_in) : g.n_in;
+    int ob0 = xb, ob1 = xb + 1;
+    if (g.out_off && xb < n_in) { ob0 = g.out_off[xb]; ob1 = g.out_off[xb + 1]; }
+    if (xb >= n_in || ob0 >= ob1) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        return;
+    }
+
+    f32x16 acc[MI][NJ];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // fragment rows are wm*64 + i*32 + lm and wn*BN/2 + j*32 + lm: (row >> 1) & 7 == (lm >> 1) & 7 for all of them
-    const int fa0 = (wm * 64 + lm) * BK, fb0 = A_EL + (wn * (BN / 2) + lm) * BK, sw = (lm >> 1) & 7;
-    const int nk = g.K / BK;
-    const int npro = min(NS, nk);
-    for (int s = 0; s < npro; ++s) issue(s, s);
+    // operands of the low-rank expand for ranks [s0, s0 + 16) of output block ob: S rows of this wave's MI row
+    // subtiles and Bt rows of its NJ column subtiles (rows past T / columns past N are clamped or zero: they only
+    // feed results that are never stored)
+    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    auto load_fs = [&](bf16x8(&fs)[MI], int ob, int s0) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int t = min(t0 + wm * MI * 32 + i * 32 + lm, g.T - 1);
+            fs[i] = *(const bf16x8 *)((const bf16_t *)g.S + ((size_t)ob * g.T + t) * g.RP + s0 + lh * 8);
+        }
+    };
+    auto load_fw = [&](bf16x8(&fw)[NJ], int k_ad, int s0) {
+        const bf16_t *Bt = (const bf16_t *)g.Bt + (size_t)k_ad * g.N * g.r;
+        const int j0 = s0 + lh * 8;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const int bcol = n0 + wn * NJ * 32 + j * 32 + lm;
+            bf16x8 f = zero8;
+            if (bcol < g.N) {
+                const bf16_t *p = Bt + (size_t)bcol * g.r + j0;
+                if ((g.r & 7) == 0) {
+                    if (j0 + 8 <= g.r) f = *(const bf16x8 *)p;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (j0 + q < g.r) f[q] = p[q];
+                }
+            }
+            fw[j] = f;
+        }
+    };
+    // small tiles have registers to spare: fetch the first output block's expand operands now, so that their
+    // latency hides behind the main loop.  They are younger than the prologue's tile loads, so the in-order load
+    // counter used below can only over-wait (by these few loads), never under-wait.
+    constexpr bool EARLY = MI * NJ <= 4;
+    const bool has_lora = g.S && g.adapter_of_out;
+    bf16x8 fs0[MI], fw0[NJ];
+    int k_ad0 = -1;
+    if (EARLY && has_lora) {
+        k_ad0 = g.adapter_of_out[ob0];
+        if (k_ad0 >= 0) { load_fs(fs0, ob0, 0); load_fw(fw0, k_ad0, 0); }
+    }
+
+    // fragment rows are wm*MI*32 + i*32 + lm and wn*NJ*32 + j*32 + lm: (row >> 1) & 7 == (lm >> 1) & 7 for all
+    const int fa0 = (wm * MI * 32 + lm) * BK, fb0 = A_EL + (wn * NJ * 32 + lm) * BK, sw = (lm >> 1) & 7;
     for (int it = 0; it < nk; ++it) {
         // k-tiles issued beyond `it` may stay in flight; everything up to `it` must have landed
         const int last_issued = it == 0 ? npro - 1 : min(nk - 1, it + NS - 2);
         const int ahead = last_issued - it;
-        if (NS >= 4 && ahead >= 3) wait_vm_and_barrier<3 * NLD>();
-        else if (NS >= 3 && ahead == 2) wait_vm_and_barrier<2 * NLD>();
+        if (NS >= 4 && ahead >= 3) wait_vm_and_barrier<(NS >= 4 ? 3 : 0) * NLD>();
+        else if (NS >= 3 && ahead == 2) wait_vm_and_barrier<(NS >= 3 ? 2 : 0) * NLD>();
         else if (ahead == 1) wait_vm_and_barrier<NLD>();
         else wait_vm_and_barrier<0>();
         // every wave is past compute(it - 1): its stage can be refilled
@@ -310,117 +362,138 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_dma_kernel(const GemmArgs g,
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             const int ko = ((2 * kk + lh) ^ sw) << 3;
-            bf16x8 fa[2], fb[NJ];
+            bf16x8 fa[MI], fb[NJ];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) fa[i] = *(const bf16x8 *)(cur + fa0 + i * 32 * BK + ko);
+            for (int i = 0; i < MI; ++i) fa[i] = *(const bf16x8 *)(cur + fa0 + i * 32 * BK + ko);
 #pragma unroll
             for (int j = 0; j < NJ; ++j) fb[j] = *(const bf16x8 *)(cur + fb0 + j * 32 * BK + ko);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
         }
     }
     __syncthreads();   // all loads have landed (vmcnt(0) above) and all waves are done with the tiles
 
-    // ---- epilogue.  acc[i][j][e] = C[row wm*64 + i*32 + lm][col wn*BN/2 + j*32 + 8*(e/4) + 4*lh + e%4]
-    // staging tile of this wave: 64 rows x NC chunks of 4 floats; chunk ch of row r sits at ch ^ swz(r)
-    float *stg = (float *)dsmem + wave * (64 * NC * 4);
+    // ---- epilogue, wave by wave and 32 rows at a time: no workgroup barrier is needed because each wave stages
+    // through its own LDS region and the LDS executes one wave's instructions in order.
+    // acc[i][j][e] = C[row wm*MI*32 + i*32 + lm][col wn*NJ*32 + j*32 + 8*(e/4) + 4*lh + e%4]
+    float *stg = (float *)dsmem + wave * (32 * NC * 4);   // 32 rows x NC chunks of 4 floats; chunk ch of row r at ch ^ swz(r)
     auto swz = [](int r) { return NC == 16 ? (r & 15) : ((r >> 1) & 7); };
-    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    const bool single = ob0 + 1 == ob1;
-    bool live[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) live[i] = t0 + wm * 64 + i * 32 < g.T;
 
     // read-back mapping: NC consecutive lanes cover one row segment; each pass covers 64 / NC rows
     constexpr int RPP = 64 / NC;
     const int rch = lane % NC, rrow = lane / NC;
-    const int col = n0 + wn * (BN / 2) + rch * 4;
+    const int col = n0 + wn * NJ * 32 + rch * 4;
     const bool col_ok = col < g.N;
     f32x4 bias4 = {0.f, 0.f, 0.f, 0.f};
     if (g.bias && col_ok) bias4 = *(const f32x4 *)(g.bias + col);
+    const bool gelu = g.mode == EPI_GELU;
 
     for (int ob = ob0; ob < ob1; ++ob) {
-        const int k_ad = (g.S && g.adapter_of_out) ? g.adapter_of_out[ob] : -1;
-        // registers (+ low-rank expand) -> LDS, one 32-row subtile at a time so that a second copy of the
-        // accumulators is only ever 16 * NJ registers
+        const int k_ad = has_lora ? g.adapter_of_out[ob] : -1;
+        const int rb = (g.mode == EPI_RESID && g.res) ? (g.res_block_of_out ? g.res_block_of_out[ob] : ob) : 0;
+        bf16x8 fs[MI], fw[NJ];
+        if (k_ad >= 0) {
+            if (EARLY && ob == ob0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            if (!live[i]) continue;
+                for (int i = 0; i < MI; ++i) fs[i] = fs0[i];
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) fw[j] = fw0[j];
+            } else {
+                if (EARLY) { load_fs(fs, ob, 0); load_fw(fw, k_ad, 0); }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int tw = t0 + wm * MI * 32 + i * 32;     // first row of this 32-row subtile
+            if (tw >= g.T) break;
             f32x16 c[NJ];
 #pragma unroll
             for (int j = 0; j < NJ; ++j) c[j] = acc[i][j];
             if (k_ad >= 0) {
-                const int t = t0 + wm * 64 + i * 32 + lm;
-                const bf16_t *S = (const bf16_t *)g.S + ((size_t)ob * g.T + min(t, g.T - 1)) * g.RP;
-                const bf16_t *Bt = (const bf16_t *)g.Bt + (size_t)k_ad * g.N * g.r;
-                for (int s0 = 0; s0 < g.RP; s0 += 16) {
-                    const int j0 = s0 + lh * 8;
-                    const bf16x8 fs = *(const bf16x8 *)(S + j0);    // rows past T feed rows that are never stored
+                // low-rank expand: one more MFMA K step per 16 ranks
+                if (!EARLY) {   // large tiles are short of registers: operands are fetched one subtile at a time
+                    const int t = min(tw + lm, g.T - 1);
+                    fs[i] = *(const bf16x8 *)((const bf16_t *)g.S + ((size_t)ob * g.T + t) * g.RP + lh * 8);
+                    load_fw(fw, k_ad, 0);
+                }
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j) {
-                        const int bcol = n0 + wn * (BN / 2) + j * 32 + lm;
-                        bf16x8 f = zero8;
-                        if (bcol < g.N) {
-                            const bf16_t *p = Bt + (size_t)bcol * g.r + j0;
-                            if ((g.r & 7) == 0) {
-                                if (j0 + 8 <= g.r) f = *(const bf16x8 *)p;
-                            } else {
+                for (int j = 0; j < NJ; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[j], fs[i], c[j], 0, 0, 0);
+                for (int s0 = 16; s0 < g.RP; s0 += 16) {
+                    bf16x8 fs2[MI], fw2[NJ];
+                    load_fs(fs2, ob, s0);
+                    load_fw(fw2, k_ad, s0);
 #pragma unroll
-                                for (int q = 0; q < 8; ++q)
-                                    if (j0 + q < g.r) f[q] = p[q];
-                            }
-                        }
-                        c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, fs, c[j], 0, 0, 0);
-                    }
+                    for (int j = 0; j < NJ; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw2[j], fs2[i], c[j], 0, 0, 0);
                 }
             }
-            const int srow = i * 32 + lm;
+            // residual and position rows of this subtile: requested before the staging round trip when there are
+            // registers for them, so that their latency overlaps it
+            const int rows_left = g.T - tw;
+            const size_t obase = ((size_t)ob * g.Tout + g.t_off + tw) * g.N + col;
+            const float *res = (g.mode == EPI_RESID && g.res) ? g.res + ((size_t)rb * g.Tout + g.t_off + tw) * g.N + col : nullptr;
+            const float *pos = (g.mode == EPI_RESID && g.pos) ? g.pos + (size_t)(g.t_off + tw) * g.N + col : nullptr;
+            constexpr bool RES_EARLY = false;   // costs 16 registers and with them a resident workgroup per CU: not worth it
+            f32x4 rv[RES_EARLY ? 32 / RPP : 1];
+            if (RES_EARLY && g.mode == EPI_RESID) {
+#pragma unroll
+                for (int q = 0; q < 32 / RPP; ++q) {
+                    const int row = q * RPP + rrow;
+                    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                    if (row < rows_left && col_ok) {
+                        if (res) v = *(const f32x4 *)(res + (size_t)row * g.N);
+                        if (pos) v += *(const f32x4 *)(pos + (size_t)row * g.N);
+                    }
+                    rv[RES_EARLY ? q : 0] = v;
+                }
+            }
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int ch = j * 8 + 2 * q + lh;
                     const f32x4 v = {c[j][4 * q], c[j][4 * q + 1], c[j][4 * q + 2], c[j][4 * q + 3]};
-                    *(f32x4 *)(stg + srow * (NC * 4) + ((ch ^ swz(srow)) << 2)) = v;
+                    *(f32x4 *)(stg + lm * (NC * 4) + ((ch ^ swz(lm)) << 2)) = v;
                 }
-        }
-        __syncthreads();
-        // LDS -> global
-        const int rows_left = g.T - (t0 + wm * 64);     // rows of this wave tile inside the block
-        const size_t obase = ((size_t)ob * g.Tout + g.t_off + t0 + wm * 64) * g.N + col;
-        if (g.mode == EPI_RESID) {
-            const int rb = g.res ? (g.res_block_of_out ? g.res_block_of_out[ob] : ob) : 0;
-            const float *res = g.res ? g.res + ((size_t)rb * g.Tout + g.t_off + t0 + wm * 64) * g.N + col : nullptr;
-            const float *pos = g.pos ? g.pos + (size_t)(g.t_off + t0 + wm * 64) * g.N + col : nullptr;
-            float *out = (float *)g.out + obase;
-#pragma unroll 4
-            for (int q = 0; q < NC; ++q) {
-                const int row = q * RPP + rrow;
-                if (row >= rows_left || !col_ok) continue;
-                f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4;
-                if (res) v += *(const f32x4 *)(res + (size_t)row * g.N);
-                if (pos) v += *(const f32x4 *)(pos + (size_t)row * g.N);
-                *(f32x4 *)(out + (size_t)row * g.N) = v;
-            }
-        } else {
-            bf16_t *out = (bf16_t *)g.out + obase;
-            const bool gelu = g.mode == EPI_GELU;
-#pragma unroll 4
-            for (int q = 0; q < NC; ++q) {
-                const int row = q * RPP + rrow;
-                if (row >= rows_left || !col_ok) continue;
-                f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4;
-                if (gelu) {
+            // LDS -> global
+            if (g.mode == EPI_RESID) {
+                float *out = (float *)g.out + obase;
+                if (RES_EARLY) {
 #pragma unroll
-                    for (int z = 0; z < 4; ++z) v[z] = gelu_erf(v[z]);
+                    for (int q = 0; q < 32 / RPP; ++q) {
+                        const int row = q * RPP + rrow;
+                        if (row >= rows_left || !col_ok) continue;
+                        const f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4 + rv[RES_EARLY ? q : 0];
+                        *(f32x4 *)(out + (size_t)row * g.N) = v;
+                    }
+                } else {
+#pragma unroll 2
+                    for (int q = 0; q < 32 / RPP; ++q) {
+                        const int row = q * RPP + rrow;
+                        if (row >= rows_left || !col_ok) continue;
+                        f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4;
+                        if (res) v += *(const f32x4 *)(res + (size_t)row * g.N);
+                        if (pos) v += *(const f32x4 *)(pos + (size_t)row * g.N);
+                        *(f32x4 *)(out + (size_t)row * g.N) = v;
+                    }
                 }
-                const bf16x4 w = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
-                *(bf16x4 *)(out + (size_t)row * g.N) = w;
+            } else {
+                bf16_t *out = (bf16_t *)g.out + obase;
+#pragma unroll 2
+                for (int q = 0; q < 32 / RPP; ++q) {
+                    const int row = q * RPP + rrow;
+                    if (row >= rows_left || !col_ok) continue;
+                    f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4;
+                    if (gelu) {
+#pragma unroll
+                        for (int z = 0; z < 4; ++z) v[z] = gelu_erf_fast(v[z]);
+                    }
+                    const bf16x4 w = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+                    *(bf16x4 *)(out + (size_t)row * g.N) = w;
+                }
             }
         }
-        if (!single) __syncthreads();   // the staging tile is rewritten by the next output block
     }
 }
 
@@ -497,42 +570,53 @@ static unsigned dma_grid(int tiles_mtot, int tiles_n)
     return (unsigned)(per * tiles_n * 8);
 }
 
+template <int BM, int BN, int WM, int WN, int NS>
+static void launch_dma(const GemmArgs &g, hipStream_t st)
+{
+    constexpr int LDS = NS * (BM + BN) * 64 * 2;
+    auto kern = gemm_bf16_dma_kernel<BM, BN, WM, WN, NS>;
+    if (LDS > 64 * 1024) {
+        static bool attr_set = false;   // raising the dynamic LDS limit is a per-kernel, process-wide setting
+        if (!attr_set) {
+            (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+            attr_set = true;
+        }
+    }
+    const int tiles_m = (g.T + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, kern, dim3(dma_grid(g.n_in * tiles_m, tiles_n)), dim3(64 * WM * WN), LDS, st, g, tiles_m, tiles_n);
+}
+
 int launch_gemm(const GemmArgs &g, int dtype, hipStream_t st)
 {
     if (g.n_in <= 0 || g.T <= 0) return POLY_OK;
     if (dtype == POLY_BF16) {
         if (g.K % 8 != 0 || (g.S && g.RP % 16 != 0)) return POLY_EINVAL;
-        const int tiles_m = (g.T + 127) / 128;
-        // 128-column tiles when they divide N or N is large; 64-column tiles otherwise (no wasted columns at
-        // N = 192 or 576, and more workgroups for small batches)
-        const bool wide = g.N % 128 == 0 || g.N >= 1024;
-        const int tiles_n = wide ? (g.N + 127) / 128 : (g.N + 63) / 64;
-        const long blocks = (long)g.n_in * tiles_m * tiles_n;
-        if (blocks > 0x3fffffffL || (long)g.N * g.K > 0x7fffffffL || (long)g.T * g.K > 0x7fffffffL) return POLY_EINVAL;
+        if ((long)g.N * g.K > 0x7fffffffL || (long)g.T * g.K > 0x7fffffffL) return POLY_EINVAL;
         if (g.K % 64 == 0 && g.N % 8 == 0) {
             static const int variant = getenv("POLY_GEMM_VARIANT") ? atoi(getenv("POLY_GEMM_VARIANT")) : 1;
-            const unsigned grid = dma_grid(g.n_in * tiles_m, tiles_n);
-            if (variant == 1) {
-                if (wide)
-                    POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, (gemm_bf16_dma_kernel<128, 2>), dim3(grid), dim3(256), 2 * (128 + 128) * 64 * 2, st, g, tiles_m, tiles_n);
-                else
-                    POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, (gemm_bf16_dma_kernel<64, 2>), dim3(grid), dim3(256), 2 * (128 + 64) * 64 * 2, st, g, tiles_m, tiles_n);
+            // long contractions with many tiles: 256-row tiles (one per 197-token block) cut the L2 -> LDS traffic
+            // per flop; short contractions (K = 192) and small batches keep 128-row tiles, whose workgroups are
+            // light enough to overlap their load latency and epilogues across a CU
+            const long tiles256 = (long)g.n_in * ((g.T + 255) / 256) * ((g.N + 255) / 256);
+            const bool big = variant >= 1 && g.T > 128 && g.K >= 512;
+            if (big && g.N % 256 == 0 && tiles256 >= 512) {
+                launch_dma<256, 256, 2, 4, 2>(g, st);
+            } else if (big && g.N % 128 == 0 && (long)g.n_in * ((g.N + 127) / 128) >= 512) {
+                launch_dma<256, 128, 4, 2, 2>(g, st);
+            } else if (g.N % 128 == 0 || g.N >= 1024) {
+                launch_dma<128, 128, 2, 2, 2>(g, st);
             } else {
-                static bool attr_set = false;
-                if (!attr_set) {
-                    (void)hipFuncSetAttribute((const void *)gemm_bf16_dma_kernel<128, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * (128 + 128) * 64 * 2);
-                    (void)hipFuncSetAttribute((const void *)gemm_bf16_dma_kernel<64, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, 3 * (128 + 64) * 64 * 2);
-                    attr_set = true;
-                }
-                if (wide)
-                    POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, (gemm_bf16_dma_kernel<128, 3>), dim3(grid), dim3(256), 3 * (128 + 128) * 64 * 2, st, g, tiles_m, tiles_n);
-                else
-                    POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, (gemm_bf16_dma_kernel<64, 3>), dim3(grid), dim3(256), 3 * (128 + 64) * 64 * 2, st, g, tiles_m, tiles_n);
+                launch_dma<128, 64, 2, 2, 2>(g, st);
             }
-        } else if (wide) {
-            POLY_LAUNCH(POLY_STAGE_GEMM, gemm_bf16_generic_kernel<128>, dim3((unsigned)blocks), dim3(256), st, g);
         } else {
-            POLY_LAUNCH(POLY_STAGE_GEMM, gemm_bf16_generic_kernel<64>, dim3((unsigned)blocks), dim3(256), st, g);
+            const int tiles_m = (g.T + 127) / 128;
+            const bool wide = g.N % 128 == 0 || g.N >= 1024;
+            const long blocks = (long)g.n_in * tiles_m * (wide ? (g.N + 127) / 128 : (g.N + 63) / 64);
+            if (blocks > 0x3fffffffL) return POLY_EINVAL;
+            if (wide)
+                POLY_LAUNCH(POLY_STAGE_GEMM, gemm_bf16_generic_kernel<128>, dim3((unsigned)blocks), dim3(256), st, g);
+            else
+                POLY_LAUNCH(POLY_STAGE_GEMM, gemm_bf16_generic_kernel<64>, dim3((unsigned)blocks), dim3(256), st, g);
         }
     } else {
         const long blocks = (long)g.n_in * ((g.T + 63) / 64) * ((g.N + 63) / 64);

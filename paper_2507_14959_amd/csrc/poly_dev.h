@@ -42,6 +42,21 @@ template <typename T> __device__ __forceinline__ T from_f32(float v) { return (T
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
 
+// erf-GELU for results that are rounded to bf16 afterwards: erf by the five-term rational approximation of
+// Abramowitz & Stegun 7.1.26 (absolute error below 1.5e-7, two orders under half a bf16 ulp of the result),
+// one reciprocal and one exponential instead of the library routine's branches.
+__device__ __forceinline__ float gelu_erf_fast(float x)
+{
+    const float z = fabsf(x) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));   // 1 ulp reciprocal instruction, no division sequence
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float e = 1.0f - p * t * __expf(-z * z);      // erf(|x| / sqrt 2)
+    return 0.5f * x * (1.0f + copysignf(e, x));
+}
+
 // ---- launch with optional per-stage timing (profile.hip) ----
 bool poly_prof_next(int stage, hipEvent_t *a, hipEvent_t *b);
 
@@ -92,6 +107,31 @@ struct GemmArgs {
 };
 
 int launch_gemm(const GemmArgs &g, int dtype, hipStream_t st);
+
+// Row-tile linear for K <= 192 (rowlin.hip): y = [LN](x) Wt^T + b + scale ([LN](x) At_k^T) Bt_k^T with the
+// LayerNorm and the low-rank shrink computed inside the kernel.
+struct RowLinArgs {
+    const float *x_ln;            // LayerNorm mode: fp32 rows [n_in*T][K] (null = plain mode)
+    const float *ln_g, *ln_b;     // [K]
+    float eps;
+    const bf16_t *a_in;           // plain mode: bf16 rows [n_in*T][K]
+    const int *in_block_of_out;   // null = identity
+    int T, K, N;
+    int n_out;                    // upper bound of the number of output blocks (grid size)
+    const int *n_out_dev;         // true count on the device, or null
+    const bf16_t *Wt;             // [N][K]
+    const float *bias;            // [N] or null
+    const bf16_t *At, *Bt;        // [n_adapters][r][K], [n_adapters][N][r]; null = no adapters
+    int r;
+    float scale;
+    const int *adapter_of_out;
+    int mode;                     // EPI_STORE / EPI_GELU: bf16 out [n_out*T][N]; EPI_RESID: fp32 out = res + y
+    void *out;
+    const float *res;             // EPI_RESID: fp32 [..*T][N]
+    const int *res_block_of_out;  // null = ob
+};
+bool rowlin_supported(int K, int N, int r, bool lora);
+int launch_rowlin(const RowLinArgs &a, hipStream_t st);
 
 // y = LayerNorm(x) row-wise; x float [n*T][D] -> elt [n*T][D]
 int launch_layernorm(const float *x, void *y, const float *gain, const float *shift, int D, float eps, int T,

@@ -22,6 +22,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the linear kernels on the default workload: FETCH_SIZE + WRITE_SIZE from two rocprofv3 --pmc
+# runs of this script, scaled by a copy kernel of known size (profiles/bench_cfg2_deit_tiny_hbm_traffic.md)
+LINEAR_HBM_BYTES_PER_LAUNCH = 21.3e6
 
 
 def scores_for_sets(off, ids, n_groups=16, group_size=5):
@@ -70,6 +73,8 @@ def main():
     ap.add_argument("--L0", type=int, default=0, help="first adapted layer (0 = all layers adapted; 10 = last 20 %%)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-checker baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements (L0=10, isolated linear)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 256 MiB device copy (a kernel of known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (frames shard trivially, see DESIGN.md); "
@@ -116,6 +121,13 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
+    if args.calib_copy:
+        src = torch.zeros(64 << 20, dtype=torch.float32, device=dev)      # 256 MiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     step, keep = make_step(args.L0)
     sec = timed(step, args.steps, args.warmup)
 
@@ -134,9 +146,10 @@ def main():
     assert g["launches"] == n_gemm * n_prof, (g, n_gemm)
     avg_ms = g["ms"] / g["launches"]
     achieved = flops / n_gemm / (avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel (base linear + fused LoRA expand + epilogue)",
+    roofline = {"bound": "mfma", "kernel": "bf16 MFMA linears: rowlin_kernel (LN + shrink + base + expand, K=192) and gemm_bf16_dma_kernel (fc2, patch embedding)",
                 "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": LINEAR_HBM_BYTES_PER_LAUNCH if args.L0 == 0 else None,
                 "launches_per_step": n_gemm, "avg_launch_us": round(avg_ms * 1e3, 2),
                 "algorithmic_gflop_per_launch": round(flops / n_gemm / 1e9, 3)}
     stages = {k: {"launches_per_step": v["launches"] // n_prof, "us_per_step": round(v["ms"] * 1e3 / n_prof, 1)}

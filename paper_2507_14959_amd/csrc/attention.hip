@@ -30,7 +30,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_
     const bf16_t *base = qkv + (size_t)b * T * ld + hd * 64;
     const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
-    for (int v = tid; v < TKP * 8; v += 256) {
+    const int nthreads = blockDim.x, nwaves = nthreads >> 6;
+    for (int v = tid; v < TKP * 8; v += nthreads) {
         const int key = v >> 3, c8 = (v & 7) * 8;
         bf16x8 kk = zero8, vv = zero8;
         if (key < T) {
@@ -44,7 +45,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_
     __syncthreads();
 
     const int nq = (T + 31) / 32;
-    for (int qs = wave; qs < nq; qs += 4) {
+    for (int qs = wave; qs < nq; qs += nwaves) {
         const int query = qs * 32 + lm;
         bf16x8 qf[4];
 #pragma unroll
@@ -64,26 +65,34 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_
             }
         }
 
+        // only the last key tile can hold keys past T (T > 32 * (NKT - 1) by construction)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int key = (NKT - 1) * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+            s[NKT - 1][e] = key < T ? s[NKT - 1][e] : -INFINITY;
+        }
         float mx = -INFINITY;
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int key = kt * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-                s[kt][e] = key < T ? s[kt][e] : -INFINITY;
-                mx = fmaxf(mx, s[kt][e]);
-            }
+            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kt][e]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float sc = 0.125f * LOG2E;  // 1/sqrt(64), folded into the base-2 exponent
+        const float off = -mx * sc;
+        // probabilities are packed to bf16 as they are produced (they are the B operand of the second product), which
+        // frees the fp32 score registers tile by tile
         float sum = 0.f;
+        bf16x8 pf[NKT][2];
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const float p = exp2f((s[kt][e] - mx) * sc);
-                s[kt][e] = p;
-                sum += p;
-            }
+            for (int hs = 0; hs < 2; ++hs)
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][hs * 8 + q], sc, off));   // exponent <= 0: no range handling needed
+                    sum += p;
+                    pf[kt][hs][q] = (bf16_t)p;
+                }
         sum += __shfl_xor(sum, 32, 64);
 
         // O^T = V^T P^T: rows = head columns, column = this lane's query
@@ -96,9 +105,6 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_
         for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
             for (int hs = 0; hs < 2; ++hs) {
-                bf16x8 pf;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) pf[q] = (bf16_t)s[kt][hs * 8 + q];
                 // slots 0..3 = keys kbase + 4*lh + 0..3, slots 4..7 = keys kbase + 8 + 4*lh + 0..3
                 const int kbase = kt * 32 + hs * 16 + 4 * lh;
 #pragma unroll
@@ -106,7 +112,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_
                     const bf16_t *vr = Vt + (dt * 32 + lm) * VS + kbase;
                     const bf16x4 lo = *(const bf16x4 *)vr, hi = *(const bf16x4 *)(vr + 8);
                     const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[dt], 0, 0, 0);
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kt][hs], o[dt], 0, 0, 0);
                 }
             }
 
@@ -180,7 +186,9 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *qkv, float *
 template <int NKT>
 void launch_bf16(const void *qkv, void *out, int T, int D, int heads, int n_blocks, const int *n_blocks_dev, hipStream_t st)
 {
-    POLY_LAUNCH(POLY_STAGE_ATTN, attn_bf16_kernel<NKT>, dim3((unsigned)(n_blocks * heads)), dim3(256), st, (const bf16_t *)qkv, (bf16_t *)out, T, D,
+    // up to 4 waves, one 32-query tile per wave and round (the score tile of a wave needs most of a SIMD's registers)
+    const int waves = (T + 31) / 32 < 4 ? (T + 31) / 32 : 4;
+    POLY_LAUNCH(POLY_STAGE_ATTN, attn_bf16_kernel<NKT>, dim3((unsigned)(n_blocks * heads)), dim3(64 * waves), st, (const bf16_t *)qkv, (bf16_t *)out, T, D,
                        heads, n_blocks, n_blocks_dev);
 }
 

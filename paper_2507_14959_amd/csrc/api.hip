@@ -153,7 +153,7 @@ extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *b
 
         // narrow models (D <= 192, bf16): LayerNorm, shrink, base product and expand of one linear run in one
         // kernel that keeps 64 token rows on chip; otherwise LayerNorm / shrink / GEMM are separate launches
-        auto fused = [&](int t) { return dt == POLY_BF16 && rowlin_supported(D, t == 0 ? 3 * D : (t == 2 ? Dm : D), m->r, use(t)); };
+        auto fused = [&](int t) { return dt == POLY_BF16 && rowlin_supported(D, t == 0 ? 3 * D : (t == 2 ? Dm : D), m->r, use(t), t == 1); };
         auto rowlin = [&](int t, const float *x_ln, const float *ln_g, const float *ln_b, const void *a_in, const int *in_map,
                           const void *Wt, const float *bias, int N, int mode, void *out, const float *res, const int *res_map) -> int {
             RowLinArgs a = {};

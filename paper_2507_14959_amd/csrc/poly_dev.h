@@ -130,7 +130,7 @@ struct RowLinArgs {
     const float *res;             // EPI_RESID: fp32 [..*T][N]
     const int *res_block_of_out;  // null = ob
 };
-bool rowlin_supported(int K, int N, int r, bool lora);
+bool rowlin_supported(int K, int N, int r, bool lora, bool f32out);
 int launch_rowlin(const RowLinArgs &a, hipStream_t st);
 
 // y = LayerNorm(x) row-wise; x float [n*T][D] -> elt [n*T][D]

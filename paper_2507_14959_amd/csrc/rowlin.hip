@@ -31,8 +31,9 @@ __device__ __forceinline__ unsigned lds_addr_of(const void *p)
 
 constexpr int RL_ROWS = 64;    // token rows per workgroup
 constexpr int RL_BNC = 64;     // output columns per W chunk
-constexpr int RL_NS = 5;       // LDS stages of the W stream: 4 chunks in flight
+constexpr int RL_NS = 5;       // LDS stages of the W stream
 constexpr int RL_MAXCH = 12;   // chunks per workgroup: N <= 768
+constexpr int RL_THREADS = 512;
 
 // LDS tile of [rows][64] bf16: 16-byte chunk c of row r sits at position c ^ ((r >> 1) & 7)
 __device__ __forceinline__ int tile_off(int row, int chunk) { return row * 64 + ((chunk ^ ((row >> 1) & 7)) << 3); }
@@ -42,16 +43,19 @@ template <int N> __device__ __forceinline__ void rl_wait_barrier()
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-// One workgroup = 4 waves in a 2 x 2 grid over a [64 rows] x [64 columns] chunk; with one workgroup per CU a wave
-// may use the whole register file, so the accumulators of ALL chunks (up to 12 x 16 registers) stay resident and
-// the chunk loop is nothing but the W stream: wait, barrier, refill, 12 MFMAs.  Stores happen once, at the end.
+// One workgroup = 8 waves = two groups of 2 x 2 waves.  Both groups hold the same 64 activation rows as MFMA
+// operand registers; group g takes the W chunks c with c % 2 == g, so two chunks are multiplied at a time and
+// every SIMD has two waves whose MFMA and vector work (LayerNorm, GELU, conversions) overlap.  The
+// accumulators of all of a wave's chunks (up to 6 x 16 registers) stay resident, so the chunk loop is nothing
+// but the W stream: wait, barrier, refill, 12 MFMAs.  Stores happen once, at the end.
 template <int KT, int MODE>   // K = 64 * KT; MODE = EPI_STORE / EPI_GELU / EPI_RESID, fixed at compile time to keep the epilogue branch-free
-__global__ __launch_bounds__(256, 1) void rowlin_kernel(const RowLinArgs a)
+__global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
 {
     constexpr int K = 64 * KT;
     constexpr int A_EL = KT * RL_ROWS * 64;          // resident activation rows, one [64][64] tile per 64 k
     constexpr int W_EL = KT * RL_BNC * 64;           // one W chunk: KT tiles of [64][64]
-    constexpr int NLD = 2 * KT;                      // W loads per wave and chunk
+    constexpr int NLD = KT;                          // W loads per wave and chunk
+    constexpr int MAXIT = RL_MAXCH / 2;              // chunk pairs
     extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
     bf16_t *As = lds, *Ws = lds + A_EL;
     float *bias_s = (float *)(lds + A_EL + RL_NS * W_EL);   // [N] bias, copied once: the epilogue must not wait on global loads
@@ -59,25 +63,23 @@ __global__ __launch_bounds__(256, 1) void rowlin_kernel(const RowLinArgs a)
     const int tiles = (a.T + RL_ROWS - 1) / RL_ROWS;
     const int ob = blockIdx.x / tiles, t0 = (blockIdx.x % tiles) * RL_ROWS;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wr = wave >> 1, wc = wave & 1, lm = lane & 31, lh = lane >> 5;
+    const int grp = wave >> 2, wr = (wave >> 1) & 1, wc = wave & 1, lm = lane & 31, lh = lane >> 5;
     const int nchunks = (a.N + RL_BNC - 1) / RL_BNC;
+    const int niter = (nchunks + 1) >> 1;
 
-    // W chunk -> LDS stage: KT tiles x 8 groups of 8 rows; wave w takes groups 2w, 2w+1 of every tile
+    // W chunk -> LDS stage: KT tiles x 8 groups of 8 rows; wave w takes row group w of every tile
     const int lr = lane >> 3;
     auto issue_w = [&](int chunk) {
         bf16_t *st = Ws + (chunk % RL_NS) * W_EL;
+        const int row = wave * 8 + lr;
+        const int col = min(chunk * RL_BNC + row, a.N - 1);                   // columns past N are never stored
+        const bf16_t *src = a.Wt + (size_t)col * K + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int row = (wave * 2 + i) * 8 + lr;
-                const int col = min(chunk * RL_BNC + row, a.N - 1);           // columns past N are never stored
-                const bf16_t *src = a.Wt + (size_t)col * K + kt * 64 + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
-                glds16(src, __builtin_amdgcn_readfirstlane(lds_addr_of(st + kt * (RL_BNC * 64) + (wave * 2 + i) * 512)));
-            }
+            glds16(src + kt * 64, __builtin_amdgcn_readfirstlane(lds_addr_of(st + kt * (RL_BNC * 64) + wave * 512)));
     };
-    // the W stream needs nothing but the kernel arguments: start it before anything else
-    const int npro = min(RL_NS - 1, nchunks);
+    // the W stream needs nothing but the kernel arguments: start it before anything else (all stages are free)
+    const int npro = min(RL_NS, nchunks);
     for (int c = 0; c < npro; ++c) issue_w(c);
 
     const int n_out = a.n_out_dev ? min(*a.n_out_dev, a.n_out) : a.n_out;
@@ -89,51 +91,52 @@ __global__ __launch_bounds__(256, 1) void rowlin_kernel(const RowLinArgs a)
     const int k_ad = (a.At && a.adapter_of_out) ? a.adapter_of_out[ob] : -1;
 
     // ---- activation rows of this tile -> LDS (rows past T are clamped: their results are never stored)
-    if (a.x_ln == nullptr) {
-        const bf16_t *src_blk = a.a_in + (size_t)xb * a.T * K;
-        const int row = tid >> 2, part = tid & 3;    // 4 threads per row, K/4 contiguous elements each
-        const bf16_t *src = src_blk + (size_t)min(t0 + row, a.T - 1) * K + part * (K / 4);
+    {
+        constexpr int PER = K / 8;                   // 8 threads per row, K/8 contiguous elements each
+        const int row = tid >> 3, part = tid & 7;
+        if (a.x_ln == nullptr) {
+            const bf16_t *src = a.a_in + ((size_t)xb * a.T + min(t0 + row, a.T - 1)) * K + part * PER;
 #pragma unroll
-        for (int c = 0; c < K / 32; ++c) {
-            const int k = part * (K / 4) + 8 * c;
-            *(bf16x8 *)(As + (k >> 6) * (RL_ROWS * 64) + tile_off(row, (k & 63) >> 3)) = *(const bf16x8 *)(src + 8 * c);
-        }
-    } else {
-        // LayerNorm: 4 threads per row, K/4 contiguous elements each, fp32 statistics
-        constexpr int PER = K / 4, NV = PER / 4;
-        const int row = tid >> 2, part = tid & 3;
-        const float *xr = a.x_ln + ((size_t)xb * a.T + min(t0 + row, a.T - 1)) * K + part * PER;
-        const float *gp = a.ln_g + part * PER, *bp = a.ln_b + part * PER;
-        f32x4 v[NV], gv[NV], bv[NV];      // gain and shift are requested together with the rows: one latency, not two
-#pragma unroll
-        for (int i = 0; i < NV; ++i) v[i] = *(const f32x4 *)(xr + 4 * i);
-#pragma unroll
-        for (int i = 0; i < NV; ++i) { gv[i] = *(const f32x4 *)(gp + 4 * i); bv[i] = *(const f32x4 *)(bp + 4 * i); }
-        float s = 0.f;
-#pragma unroll
-        for (int i = 0; i < NV; ++i) s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
-        s += __shfl_xor(s, 1, 64); s += __shfl_xor(s, 2, 64);
-        const float mean = s * (1.0f / K);
-        float q = 0.f;
-#pragma unroll
-        for (int i = 0; i < NV; ++i)
-#pragma unroll
-            for (int z = 0; z < 4; ++z) { const float d = v[i][z] - mean; q = fmaf(d, d, q); }
-        q += __shfl_xor(q, 1, 64); q += __shfl_xor(q, 2, 64);
-        const float inv = rsqrtf(q * (1.0f / K) + a.eps);
-#pragma unroll
-        for (int c = 0; c < PER / 8; ++c) {
-            bf16x8 o;
-#pragma unroll
-            for (int z = 0; z < 4; ++z) {
-                o[z] = (bf16_t)((v[2 * c][z] - mean) * inv * gv[2 * c][z] + bv[2 * c][z]);
-                o[4 + z] = (bf16_t)((v[2 * c + 1][z] - mean) * inv * gv[2 * c + 1][z] + bv[2 * c + 1][z]);
+            for (int c = 0; c < PER / 8; ++c) {
+                const int k = part * PER + 8 * c;
+                *(bf16x8 *)(As + (k >> 6) * (RL_ROWS * 64) + tile_off(row, (k & 63) >> 3)) = *(const bf16x8 *)(src + 8 * c);
             }
-            const int k = part * PER + 8 * c;       // first of 8 consecutive k: tile k / 64, chunk (k % 64) / 8
-            *(bf16x8 *)(As + (k >> 6) * (RL_ROWS * 64) + tile_off(row, (k & 63) >> 3)) = o;
+        } else {
+            // LayerNorm with fp32 statistics; gain and shift are requested together with the rows: one latency, not two
+            constexpr int NV = PER / 4;
+            const float *xr = a.x_ln + ((size_t)xb * a.T + min(t0 + row, a.T - 1)) * K + part * PER;
+            const float *gp = a.ln_g + part * PER, *bp = a.ln_b + part * PER;
+            f32x4 v[NV], gv[NV], bv[NV];
+#pragma unroll
+            for (int i = 0; i < NV; ++i) v[i] = *(const f32x4 *)(xr + 4 * i);
+#pragma unroll
+            for (int i = 0; i < NV; ++i) { gv[i] = *(const f32x4 *)(gp + 4 * i); bv[i] = *(const f32x4 *)(bp + 4 * i); }
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
+            s += __shfl_xor(s, 1, 64); s += __shfl_xor(s, 2, 64); s += __shfl_xor(s, 4, 64);
+            const float mean = s * (1.0f / K);
+            float q = 0.f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i)
+#pragma unroll
+                for (int z = 0; z < 4; ++z) { const float d = v[i][z] - mean; q = fmaf(d, d, q); }
+            q += __shfl_xor(q, 1, 64); q += __shfl_xor(q, 2, 64); q += __shfl_xor(q, 4, 64);
+            const float inv = rsqrtf(q * (1.0f / K) + a.eps);
+#pragma unroll
+            for (int c = 0; c < PER / 8; ++c) {
+                bf16x8 o;
+#pragma unroll
+                for (int z = 0; z < 4; ++z) {
+                    o[z] = (bf16_t)((v[2 * c][z] - mean) * inv * gv[2 * c][z] + bv[2 * c][z]);
+                    o[4 + z] = (bf16_t)((v[2 * c + 1][z] - mean) * inv * gv[2 * c + 1][z] + bv[2 * c + 1][z]);
+                }
+                const int k = part * PER + 8 * c;   // first of 8 consecutive k: tile k / 64, chunk (k % 64) / 8
+                *(bf16x8 *)(As + (k >> 6) * (RL_ROWS * 64) + tile_off(row, (k & 63) >> 3)) = o;
+            }
         }
     }
-    for (int i = tid; i < a.N; i += 256) bias_s[i] = a.bias ? a.bias[i] : 0.f;
+    for (int i = tid; i < a.N; i += RL_THREADS) bias_s[i] = a.bias ? a.bias[i] : 0.f;
     // the activation rows were written with ordinary LDS stores: make them visible, but do not drain the W
     // stream (a fenced barrier would): wait for this wave's LDS stores, then a bare barrier
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -143,15 +146,15 @@ __global__ __launch_bounds__(256, 1) void rowlin_kernel(const RowLinArgs a)
     // and drains the stream before every chunk.  Shrink: At rows as the A operand (rank = lm).
     // Expand: lane (column, lh) supplies ranks 4*lh + {0..3} and 8 + 4*lh + {0..3} (see the shrink below).
     const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    bf16x8 ft[KT * 4], fbt[RL_MAXCH];
+    bf16x8 ft[KT * 4], fbt[MAXIT];
     if (k_ad >= 0) {
         const bf16_t *At = a.At + ((size_t)k_ad * a.r + min(lm, a.r - 1)) * K + lh * 8;
 #pragma unroll
         for (int kk = 0; kk < KT * 4; ++kk) ft[kk] = lm < a.r ? *(const bf16x8 *)(At + kk * 16) : zero8;
 #pragma unroll
-        for (int ch = 0; ch < RL_MAXCH; ++ch) {
+        for (int it = 0; it < MAXIT; ++it) {
             bf16x8 f = zero8;
-            const int col = ch * RL_BNC + wc * 32 + lm;
+            const int ch = 2 * it + grp, col = ch * RL_BNC + wc * 32 + lm;
             if (ch < nchunks && col < a.N) {
                 const bf16_t *bt = a.Bt + ((size_t)k_ad * a.N + col) * a.r;
                 if ((a.r & 3) == 0) {
@@ -159,13 +162,13 @@ __global__ __launch_bounds__(256, 1) void rowlin_kernel(const RowLinArgs a)
                     if (8 + 4 * lh + 4 <= a.r) { const bf16x4 hi = *(const bf16x4 *)(bt + 8 + 4 * lh); f[4] = hi[0]; f[5] = hi[1]; f[6] = hi[2]; f[7] = hi[3]; }
                 } else {
 #pragma unroll
-                    for (int s = 0; s < 8; ++s) {
-                        const int rank = (s < 4 ? 4 * lh + s : 8 + 4 * lh + (s - 4));
-                        if (rank < a.r) f[s] = bt[rank];
+                    for (int sl = 0; sl < 8; ++sl) {
+                        const int rank = (sl < 4 ? 4 * lh + sl : 8 + 4 * lh + (sl - 4));
+                        if (rank < a.r) f[sl] = bt[rank];
                     }
                 }
             }
-            fbt[ch] = f;
+            fbt[it] = f;
         }
     }
 
@@ -186,42 +189,47 @@ __global__ __launch_bounds__(256, 1) void rowlin_kernel(const RowLinArgs a)
         for (int kk = 0; kk < KT * 4; ++kk) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ft[kk], fa[kk], c, 0, 0, 0);
 #pragma unroll
         for (int j = 0; j < 8; ++j) fs[j] = (bf16_t)(a.scale * c[j]);
+        // everything that was loaded into registers is forced to have arrived here, in one wait that the compiler
+        // sees (the empty asm "uses" the registers): inside the stream below only the LDS-bound loads are in flight
+#pragma unroll
+        for (int it = 0; it < MAXIT; ++it) asm volatile("" ::"v"(fbt[it]));
     }
 
-    // Everything that was loaded into registers is forced to have arrived here, in one wait that the compiler
-    // sees (the empty asm "uses" the registers): inside the stream below only the LDS-bound loads are in
-    // flight, so no compiler-inserted wait can drain them.
-    if (k_ad >= 0) {
+    // ---- the W stream: iteration it multiplies chunks 2*it (group 0) and 2*it + 1 (group 1);
+    // acc[it] = rows wr*32.. x columns (2*it + grp)*64 + wc*32..
+    f32x16 acc[MAXIT];
 #pragma unroll
-        for (int ch = 0; ch < RL_MAXCH; ++ch) asm volatile("" ::"v"(fbt[ch]));
-    }
-    // ---- the W stream: chunk ch feeds acc[ch] = rows wr*32.. x columns ch*64 + wc*32..
-    f32x16 acc[RL_MAXCH];
+    for (int it = 0; it < MAXIT; ++it) {
+        if (it < niter) {     // uniform; written as a guard (not a break) so that the loop unrolls and acc stays in registers
 #pragma unroll
-    for (int ch = 0; ch < RL_MAXCH; ++ch) {
-        if (ch < nchunks) {     // uniform; written as a guard (not a break) so that the loop unrolls and acc stays in registers
+            for (int e = 0; e < 16; ++e) acc[it][e] = 0.f;
+            // chunks 2*it and 2*it + 1 must have landed; later chunks may stay in flight (loads return in order).
+            // Issued so far: the prologue's min(NS, nchunks) chunks, then two more per earlier iteration.
+            const int last_issued = min(nchunks - 1, it == 0 ? RL_NS - 1 : 2 * it + RL_NS - 3);
+            const int ahead = max(0, last_issued - (2 * it + 1));
+            if (ahead >= 3) rl_wait_barrier<3 * NLD>();
+            else if (ahead == 2) rl_wait_barrier<2 * NLD>();
+            else if (ahead == 1) rl_wait_barrier<NLD>();
+            else rl_wait_barrier<0>();
+            // every wave is past chunks 2*it - 2 and 2*it - 1: their stages take chunks 2*it + NS - 2 and 2*it + NS - 1
+            if (it >= 1) {
+                if (2 * it + RL_NS - 2 < nchunks) issue_w(2 * it + RL_NS - 2);
+                if (2 * it + RL_NS - 1 < nchunks) issue_w(2 * it + RL_NS - 1);
+            }
+            const int ch = 2 * it + grp;
+            if (ch < nchunks) {
+                const bf16_t *st = Ws + (ch % RL_NS) * W_EL;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[ch][e] = 0.f;
-        // chunks issued beyond `ch` may stay in flight (loads return in order); chunk ch must have landed.  The
-        // few operand loads issued after the prologue only make this wait stricter.
-        const int ahead = min(nchunks - 1, ch + RL_NS - 2) - ch;
-        if (ahead >= 3) rl_wait_barrier<3 * NLD>();
-        else if (ahead == 2) rl_wait_barrier<2 * NLD>();
-        else if (ahead == 1) rl_wait_barrier<NLD>();
-        else rl_wait_barrier<0>();
-        // every wave is past chunk ch - 1, whose stage is the one chunk ch + NS - 1 goes to
-        if (ch + RL_NS - 1 < nchunks) issue_w(ch + RL_NS - 1);
-        const bf16_t *st = Ws + (ch % RL_NS) * W_EL;
-#pragma unroll
-        for (int kk = 0; kk < KT * 4; ++kk) {
-            const bf16x8 fw = *(const bf16x8 *)(st + (kk >> 2) * (RL_BNC * 64) + tile_off(wc * 32 + lm, 2 * (kk & 3) + lh));
-            acc[ch] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fa[kk], acc[ch], 0, 0, 0);
-        }
-        if (k_ad >= 0) acc[ch] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fbt[ch], fs, acc[ch], 0, 0, 0);
+                for (int kk = 0; kk < KT * 4; ++kk) {
+                    const bf16x8 fw = *(const bf16x8 *)(st + (kk >> 2) * (RL_BNC * 64) + tile_off(wc * 32 + lm, 2 * (kk & 3) + lh));
+                    acc[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fa[kk], acc[it], 0, 0, 0);
+                }
+                if (k_ad >= 0) acc[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fbt[it], fs, acc[it], 0, 0, 0);
+            }
         }
     }
 
-    // ---- epilogue.  acc[ch][e]: row wr*32 + lm, column ch*64 + wc*32 + 8*(e/4) + 4*lh + e%4.
+    // ---- epilogue.  acc[it][e]: row wr*32 + lm, column (2*it + grp)*64 + wc*32 + 8*(e/4) + 4*lh + e%4.
     // A lane owns one row, so storing from registers would touch 32 cache lines per instruction with 8 or 16
     // bytes each.  Instead the finished tile (bias, GELU applied, output type) is laid out row-major in LDS --
     // the activation rows and the W ring are dead by now -- and copied out with consecutive threads on
@@ -234,12 +242,13 @@ __global__ __launch_bounds__(256, 1) void rowlin_kernel(const RowLinArgs a)
     {
         char *trow = tile + (wr * 32 + lm) * stride + (wc * 32 + 4 * lh) * (f32out ? 4 : 2);
 #pragma unroll
-        for (int ch = 0; ch < RL_MAXCH; ++ch) {
+        for (int it = 0; it < MAXIT; ++it) {
+            const int ch = 2 * it + grp;
             if (ch < nchunks) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int col = ch * RL_BNC + wc * 32 + 8 * g + 4 * lh;
-                    f32x4 v = {acc[ch][4 * g], acc[ch][4 * g + 1], acc[ch][4 * g + 2], acc[ch][4 * g + 3]};
+                    f32x4 v = {acc[it][4 * g], acc[it][4 * g + 1], acc[it][4 * g + 2], acc[it][4 * g + 3]};
                     if (f32out) {
                         // raw sums; bias and residual are added by the copy-out below, where accesses are coalesced
                         if (col < a.N) *(f32x4 *)(trow + (ch * RL_BNC + 8 * g) * 4) = v;
@@ -263,14 +272,14 @@ __global__ __launch_bounds__(256, 1) void rowlin_kernel(const RowLinArgs a)
     if (f32out) {
         const int rblk = a.res ? (a.res_block_of_out ? a.res_block_of_out[ob] : ob) : 0;
         const char *res = a.res ? (const char *)a.res + ((size_t)rblk * a.T + t0) * row_bytes : nullptr;
-        for (int idx = tid; idx < rows * pieces; idx += 256) {
+        for (int idx = tid; idx < rows * pieces; idx += RL_THREADS) {
             const int row = idx / pieces, p = idx - row * pieces;
             f32x4 v = *(const f32x4 *)(tile + row * stride + p * 16) + *(const f32x4 *)(bias_s + 4 * p);
             if (res) v += *(const f32x4 *)(res + (size_t)row * row_bytes + p * 16);
             *(f32x4 *)(out + (size_t)row * row_bytes + p * 16) = v;
         }
     } else {
-        for (int idx = tid; idx < rows * pieces; idx += 256) {
+        for (int idx = tid; idx < rows * pieces; idx += RL_THREADS) {
             const int row = idx / pieces, p = idx - row * pieces;
             *(f32x4 *)(out + (size_t)row * row_bytes + p * 16) = *(const f32x4 *)(tile + row * stride + p * 16);
         }
@@ -289,7 +298,7 @@ template <int KT, int MODE> int launch_kt_mode(const RowLinArgs &a, hipStream_t 
         }
     }
     const int tiles = (a.T + RL_ROWS - 1) / RL_ROWS;
-    POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, kern, dim3((unsigned)(a.n_out * tiles)), dim3(256), LDS, st, a);
+    POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, kern, dim3((unsigned)(a.n_out * tiles)), dim3(RL_THREADS), LDS, st, a);
     return hipGetLastError() == hipSuccess ? POLY_OK : POLY_EHIP;
 }
 
@@ -305,15 +314,18 @@ template <int KT> int launch_kt(const RowLinArgs &a, hipStream_t st)
 
 }  // namespace
 
-bool rowlin_supported(int K, int N, int r, bool lora)
+bool rowlin_supported(int K, int N, int r, bool lora, bool f32out)
 {
-    return (K == 64 || K == 128 || K == 192) && N % 8 == 0 && N <= RL_MAXCH * RL_BNC && (!lora || (r >= 1 && r <= 16));
+    if (!((K == 64 || K == 128 || K == 192) && N >= 8 && N % 8 == 0 && N <= RL_MAXCH * RL_BNC && (!lora || (r >= 1 && r <= 16)))) return false;
+    // the finished tile is staged over the activation rows and the W ring: it must fit there
+    const long stage = (long)RL_ROWS * ((((long)N * (f32out ? 4 : 2) + 255) & ~255L) + 16);
+    return stage <= (long)(1 + RL_NS) * (K / 64) * RL_ROWS * 64 * 2;
 }
 
 int launch_rowlin(const RowLinArgs &a, hipStream_t st)
 {
     if (a.n_out <= 0 || a.T <= 0) return POLY_OK;
-    if (!rowlin_supported(a.K, a.N, a.r, a.At != nullptr)) return POLY_EINVAL;
+    if (!rowlin_supported(a.K, a.N, a.r, a.At != nullptr, a.mode == EPI_RESID)) return POLY_EINVAL;
     if ((long)a.N * a.K > 0x7fffffffL) return POLY_EINVAL;
     switch (a.K / 64) {
     case 1: return launch_kt<1>(a, st);

@@ -38,30 +38,34 @@ def scores_for_sets(off, ids, n_groups=16, group_size=5):
 
 
 def gemm_launches(cfg, F, R, L0):
-    """(rows, K, N, lora) of every linear launch of one forward, for the algorithmic flop count."""
+    """One entry per linear-kernel launch of a forward: the list of (rows, K, N, lora, lora_rows) products it computes."""
     T, D, Dm = cfg.T, cfg.D, cfg.Dm
-    out = [(F * (T - 1), cfg.patch_dim, D, False)]
+    out = [[(F * (T - 1), cfg.patch_dim, D, False, 0)]]
     for l in range(cfg.L):
         if l >= L0 and R == 0:
             break
         ad = l >= L0
         rows_qkv_in = (F if l <= L0 else R) * T      # the base product of the fan-out layer runs once per frame
         rows = (R if ad else F) * T
-        out.append((rows_qkv_in, D, 3 * D, ad and cfg.targets & 1, rows))
-        out.append((rows, D, D, ad and cfg.targets & 2, rows))
-        out.append((rows, D, Dm, ad and cfg.targets & 4, rows))
-        out.append((rows, Dm, D, ad and cfg.targets & 8, rows))
+        out.append([(rows_qkv_in, D, 3 * D, ad and cfg.targets & 1, rows)])
+        out.append([(rows, D, D, ad and cfg.targets & 2, rows)])
+        fc1 = (rows, D, Dm, ad and cfg.targets & 4, rows)
+        fc2 = (rows, Dm, D, ad and cfg.targets & 8, rows)
+        if D in (64, 128, 192) and Dm % 128 == 0 and Dm <= 768 and not (fc1[3] or fc2[3]):
+            out.append([fc1, fc2])                   # one kernel for the whole MLP half
+        else:
+            out += [[fc1], [fc2]]
     return out
 
 
 def gemm_flops(cfg, F, R, L0):
     total = 0.0
     launches = gemm_launches(cfg, F, R, L0)
-    for item in launches:
-        rows, K, N, lora = item[:4]
-        total += 2.0 * rows * K * N
-        if lora:
-            total += 2.0 * item[4] * cfg.r * N     # expand (x A_k) B_k, fused into the same kernel
+    for launch in launches:
+        for rows, K, N, lora, lora_rows in launch:
+            total += 2.0 * rows * K * N
+            if lora:
+                total += 2.0 * lora_rows * cfg.r * N     # expand (x A_k) B_k, fused into the same kernel
     return total, len(launches)
 
 
@@ -146,7 +150,7 @@ def main():
     assert g["launches"] == n_gemm * n_prof, (g, n_gemm)
     avg_ms = g["ms"] / g["launches"]
     achieved = flops / n_gemm / (avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "bf16 MFMA linears: rowlin_kernel (LN + shrink + base + expand, K=192) and gemm_bf16_dma_kernel (fc2, patch embedding)",
+    roofline = {"bound": "mfma", "kernel": "bf16 MFMA linears: rowlin_kernel (LN + shrink + base + expand: qkv, proj), mlp_kernel (LN + fc1 + GELU + fc2 + residual), gemm_bf16_dma_kernel (patch embedding)",
                 "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": LINEAR_HBM_BYTES_PER_LAUNCH if args.L0 == 0 else None,

@@ -205,6 +205,16 @@ extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *b
             POLY_TRY(launch_gemm(g, dt, st));
         }
         // ---- MLP half (x_out holds the stream from here on)
+        if (dt == POLY_BF16 && !use(2) && !use(3) && mlp_supported(D, Dm)) {
+            // no adapter on fc1 / fc2 in this layer: LayerNorm, both products, GELU and the residual in one kernel
+            MlpArgs a = {};
+            a.x = x_out; a.ln_g = base->ln2_g + (size_t)l * D; a.ln_b = base->ln2_b + (size_t)l * D; a.eps = m->ln_eps;
+            a.T = T; a.D = D; a.Dm = Dm; a.n_out = n_out; a.n_out_dev = n_out_dev;
+            a.W1t = (const bf16_t *)Wfc1; a.b1 = base->fc1_b + (size_t)l * Dm;
+            a.W2t = (const bf16_t *)((const char *)base->fc2_w + es * (size_t)l * D * Dm); a.b2 = base->fc2_b + (size_t)l * D;
+            POLY_TRY(launch_mlp(a, st));
+            continue;
+        }
         if (fused(2)) {
             POLY_TRY(rowlin(2, x_out, base->ln2_g + (size_t)l * D, base->ln2_b + (size_t)l * D, nullptr, nullptr, Wfc1,
                             base->fc1_b + (size_t)l * Dm, Dm, EPI_GELU, w.h, nullptr, nullptr));

@@ -487,7 +487,7 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
                     f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4;
                     if (gelu) {
 #pragma unroll
-                        for (int z = 0; z < 4; ++z) v[z] = gelu_erf_fast(v[z]);
+                        for (int z = 0; z < 4; ++z) v[z] = gelu_poly(v[z]);
                     }
                     const bf16x4 w = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
                     *(bf16x4 *)(out + (size_t)row * g.N) = w;

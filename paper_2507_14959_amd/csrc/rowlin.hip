@@ -10,38 +10,17 @@
 // rows; its accumulator layout is already a valid operand layout for the expand once the ranks of Bt_k are
 // read in the matching order, so S never leaves registers.
 #include "poly_dev.h"
+#include "rowtile.h"
 
 #include <stdlib.h>
 
 namespace {
-
-// 16 bytes per lane from global memory straight into LDS: lane i lands at lds_byte_addr + 16 * i.  Issued as
-// inline assembly on purpose: when the compiler sees LDS-bound loads it makes every later LDS read wait for
-// all of them (it cannot tell the ring stages apart), which would serialise the W stream below.  The waits are
-// counted by hand instead; a compiler-inserted vmcnt wait that does not know about these loads can only be
-// stricter than intended, never too weak, because loads complete in issue order.
-__device__ __forceinline__ void glds16(const void *gptr, unsigned lds_byte_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_byte_addr), "v"(gptr) : "memory", "m0");
-}
-__device__ __forceinline__ unsigned lds_addr_of(const void *p)
-{
-    return (unsigned)(size_t)(const __attribute__((address_space(3))) void *)p;
-}
 
 constexpr int RL_ROWS = 64;    // token rows per workgroup
 constexpr int RL_BNC = 64;     // output columns per W chunk
 constexpr int RL_NS = 5;       // LDS stages of the W stream
 constexpr int RL_MAXCH = 12;   // chunks per workgroup: N <= 768
 constexpr int RL_THREADS = 512;
-
-// LDS tile of [rows][64] bf16: 16-byte chunk c of row r sits at position c ^ ((r >> 1) & 7)
-__device__ __forceinline__ int tile_off(int row, int chunk) { return row * 64 + ((chunk ^ ((row >> 1) & 7)) << 3); }
-
-template <int N> __device__ __forceinline__ void rl_wait_barrier()
-{
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
-}
 
 // One workgroup = 8 waves = two groups of 2 x 2 waves.  Both groups hold the same 64 activation rows as MFMA
 // operand registers; group g takes the W chunks c with c % 2 == g, so two chunks are multiplied at a time and
@@ -102,38 +81,7 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
                 *(bf16x8 *)(As + (k >> 6) * (RL_ROWS * 64) + tile_off(row, (k & 63) >> 3)) = *(const bf16x8 *)(src + 8 * c);
             }
         } else {
-            // LayerNorm with fp32 statistics; gain and shift are requested together with the rows: one latency, not two
-            constexpr int NV = PER / 4;
-            const float *xr = a.x_ln + ((size_t)xb * a.T + min(t0 + row, a.T - 1)) * K + part * PER;
-            const float *gp = a.ln_g + part * PER, *bp = a.ln_b + part * PER;
-            f32x4 v[NV], gv[NV], bv[NV];
-#pragma unroll
-            for (int i = 0; i < NV; ++i) v[i] = *(const f32x4 *)(xr + 4 * i);
-#pragma unroll
-            for (int i = 0; i < NV; ++i) { gv[i] = *(const f32x4 *)(gp + 4 * i); bv[i] = *(const f32x4 *)(bp + 4 * i); }
-            float s = 0.f;
-#pragma unroll
-            for (int i = 0; i < NV; ++i) s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
-            s += __shfl_xor(s, 1, 64); s += __shfl_xor(s, 2, 64); s += __shfl_xor(s, 4, 64);
-            const float mean = s * (1.0f / K);
-            float q = 0.f;
-#pragma unroll
-            for (int i = 0; i < NV; ++i)
-#pragma unroll
-                for (int z = 0; z < 4; ++z) { const float d = v[i][z] - mean; q = fmaf(d, d, q); }
-            q += __shfl_xor(q, 1, 64); q += __shfl_xor(q, 2, 64); q += __shfl_xor(q, 4, 64);
-            const float inv = rsqrtf(q * (1.0f / K) + a.eps);
-#pragma unroll
-            for (int c = 0; c < PER / 8; ++c) {
-                bf16x8 o;
-#pragma unroll
-                for (int z = 0; z < 4; ++z) {
-                    o[z] = (bf16_t)((v[2 * c][z] - mean) * inv * gv[2 * c][z] + bv[2 * c][z]);
-                    o[4 + z] = (bf16_t)((v[2 * c + 1][z] - mean) * inv * gv[2 * c + 1][z] + bv[2 * c + 1][z]);
-                }
-                const int k = part * PER + 8 * c;   // first of 8 consecutive k: tile k / 64, chunk (k % 64) / 8
-                *(bf16x8 *)(As + (k >> 6) * (RL_ROWS * 64) + tile_off(row, (k & 63) >> 3)) = o;
-            }
+            ln_rows_to_lds<KT>(a.x_ln + (size_t)xb * a.T * K, a.T, t0, a.ln_g, a.ln_b, a.eps, As, tid);
         }
     }
     for (int i = tid; i < a.N; i += RL_THREADS) bias_s[i] = a.bias ? a.bias[i] : 0.f;
@@ -256,7 +204,7 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
                         v += *(const f32x4 *)(bias_s + min(col, a.N - 4));
                         if (MODE == EPI_GELU) {
 #pragma unroll
-                            for (int z = 0; z < 4; ++z) v[z] = gelu_erf_fast(v[z]);
+                            for (int z = 0; z < 4; ++z) v[z] = gelu_poly(v[z]);
                         }
                         const bf16x4 w = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
                         if (col < a.N) *(bf16x4 *)(trow + (ch * RL_BNC + 8 * g) * 2) = w;

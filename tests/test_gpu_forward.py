@@ -3,6 +3,8 @@
 Tolerances (max-abs on logits): 1e-4 in fp32, 2e-2 in bf16 -- the checker is the exact result on the
 same bf16-valued parameters; the GPU rounds activations to bf16 between stages and accumulates in fp32.
 """
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -76,8 +78,15 @@ def test_position_invariance_is_bitwise_and_zero_B_is_bare_backbone():
     wz = {k: (np.zeros_like(v) if k.startswith("B_") else v) for k, v in w.items()}
     z = binding.run_forward(binding.DeviceModel(cfg, wz), fr, off, ids)["logits"]
     bare = binding.run_forward(binding.DeviceModel(cfg, w, L0=cfg.L), fr, off, ids)["logits"]
-    # same frame -> same bare logits up to the head that reads them; compare through the checker's bar
-    assert np.abs(z - bare).max() < 1e-6
+    # Adapters on all four linears send the MLP half through other kernels than the bare backbone takes (the
+    # fused MLP kernel has no low-rank branch): same mathematics, other summation order, so only close.
+    assert np.abs(z - bare).max() < 5e-3
+    # Adapters on qkv and proj only: every layer runs the same kernels with or without the adapters, and a zero
+    # B adds exact zeros to the accumulators.
+    cfg2 = dataclasses.replace(cfg, targets=synth.TGT_QKV | synth.TGT_PROJ)
+    z2 = binding.run_forward(binding.DeviceModel(cfg2, wz), fr, off, ids)["logits"]
+    bare2 = binding.run_forward(binding.DeviceModel(cfg2, w, L0=cfg.L), fr, off, ids)["logits"]
+    assert np.abs(z2 - bare2).max() < 1e-6 and np.abs(bare2 - bare).max() < 1e-6
 
 
 @pytest.mark.parametrize("L0", [0, 10])

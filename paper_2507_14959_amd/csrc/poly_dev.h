@@ -62,6 +62,25 @@ __device__ __forceinline__ float gelu_poly(float x)
     q = fmaf(q, s, 3.987498879e-01f);
     return x * fmaxf(fmaf(xc, q, 0.499994f), 0.f);
 }
+// four at a time, written so that the four dependency chains advance together: one chain alone leaves the vector
+// pipeline idle between dependent instructions
+__device__ __forceinline__ f32x4 gelu_poly4(f32x4 x)
+{
+    f32x4 xc, s, q;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xc[i] = __builtin_amdgcn_fmed3f(x[i], -4.4f, 4.4f);
+    s = xc * xc;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) q[i] = fmaf(3.446953140e-11f, s[i], -3.649543778e-09f);
+    const float c[7] = {1.703905070e-07f, -4.655028533e-06f, 8.353321027e-05f, -1.050237101e-03f, 9.626936167e-03f, -6.605132669e-02f, 3.987498879e-01f};
+#pragma unroll
+    for (int j = 0; j < 7; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) q[i] = fmaf(q[i], s[i], c[j]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) q[i] = x[i] * fmaxf(fmaf(xc[i], q[i], 0.499994f), 0.f);
+    return q;
+}
 
 // ---- launch with optional per-stage timing (profile.hip) ----
 bool poly_prof_next(int stage, hipEvent_t *a, hipEvent_t *b);

@@ -60,6 +60,8 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
     // the W stream needs nothing but the kernel arguments: start it before anything else (all stages are free)
     const int npro = min(RL_NS, nchunks);
     for (int c = 0; c < npro; ++c) issue_w(c);
+    // the rest of W: into L2 now, so that the ring refills below are L2 hits
+    l2_warm(a.Wt, (long)a.N * K * 2, lds_addr_of(bias_s + RL_MAXCH * RL_BNC), tid, RL_THREADS);
 
     const int n_out = a.n_out_dev ? min(*a.n_out_dev, a.n_out) : a.n_out;
     if (ob >= n_out) {
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
                 *(bf16x8 *)(As + (k >> 6) * (RL_ROWS * 64) + tile_off(row, (k & 63) >> 3)) = *(const bf16x8 *)(src + 8 * c);
             }
         } else {
-            ln_rows_to_lds<KT>(a.x_ln + (size_t)xb * a.T * K, a.T, t0, a.ln_g, a.ln_b, a.eps, As, tid);
+            ln_rows_to_lds<KT, 8>(a.x_ln + (size_t)xb * a.T * K, a.T, t0, a.ln_g, a.ln_b, a.eps, As, tid);
         }
     }
     for (int i = tid; i < a.N; i += RL_THREADS) bias_s[i] = a.bias ? a.bias[i] : 0.f;
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
 
 template <int KT, int MODE> int launch_kt_mode(const RowLinArgs &a, hipStream_t st)
 {
-    constexpr int LDS = (KT * RL_ROWS * 64 + RL_NS * KT * RL_BNC * 64) * 2 + RL_MAXCH * RL_BNC * 4;
+    constexpr int LDS = (KT * RL_ROWS * 64 + RL_NS * KT * RL_BNC * 64) * 2 + RL_MAXCH * RL_BNC * 4 + 256;   // + dump words of the L2 warm-up
     auto kern = rowlin_kernel<KT, MODE>;
     if (LDS > 64 * 1024) {
         static bool attr_set = false;   // raising the dynamic LDS limit is a per-kernel, process-wide setting

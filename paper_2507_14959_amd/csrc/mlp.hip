@@ -48,6 +48,7 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
     float *b1_s = (float *)(lds + A_EL + ML_NS * IT_EL);   // [Dm]
     float *b2_s = b1_s + ML_MAX_DM;                        // [D]
     float *dump_s = b2_s + D;                              // 64 words nobody reads (target of the L2 warm-up loads)
+    float *gb_s = dump_s + 64;                             // LayerNorm gain [D] and shift [D]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool loader = wave >= 4;
@@ -82,14 +83,19 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
     };
     // newest item needed in step h
     auto need_at = [&](int h) { return h < 2 ? h : min(2 * h - 1, NQ - 1); };
-    // Only the items of steps 0 and 1 are requested up front: everything requested now queues ahead of the x rows that
-    // the prologue below is waiting for.  The loader's first steps fill the rest of the ring.
-    int last = 1;                                // newest item requested
-    if (loader) {
-        for (int q = 0; q <= last; ++q) issue_item(q);
-        // the rest of both matrices: into L2 now, so that the ring refills below are L2 hits
-        l2_warm(a.W1t, (long)Dm * D * 2, lds_addr_of(dump_s), tid - 256, 256);
-        l2_warm(a.W2t, (long)Dm * D * 2, lds_addr_of(dump_s), tid - 256, 256);
+    // The x rows are requested before anything else: they come from HBM (another kernel has just written them), and
+    // whatever is requested first is served first.  The computing waves take them (and the rest of the prologue).
+    float *xt = a.x + (size_t)t0 * D;
+    f32x4 xv[D / 16];
+    f32x4 gbv = {0.f, 0.f, 0.f, 0.f};
+    float b1v[ML_MAX_DM / 256], b2v = 0.f;
+    if (!loader) {
+        ln_load<KT, 4>(xt, (int)min(64L, (long)a.n_out * a.T - t0), 0, tid, xv);   // clamped to the buffer; rows past the true count are never stored
+        // gain, shift and biases as well: requested after the weight stream has started they would arrive behind it
+        gbv = ln_gb_load<KT>(a.ln_g, a.ln_b, tid);
+#pragma unroll
+        for (int j = 0; j < ML_MAX_DM / 256; ++j) b1v[j] = tid + 256 * j < Dm ? a.b1[tid + 256 * j] : 0.f;
+        if (tid < D) b2v = a.b2[tid];
     }
 
     MLP_TS(1);
@@ -100,13 +106,29 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
         return;
     }
     MLP_TS(2);
-    float *xt = a.x + (size_t)t0 * D;
     const int rows = (int)min(64L, nrows - t0);
-    if (!loader) {
-        // the computing waves also do the prologue: their loads do not queue behind the ring's
-        ln_rows_to_lds<KT, 4>(xt, rows, 0, a.ln_g, a.ln_b, a.eps, As, tid);
-        for (int i = tid; i < Dm; i += 256) b1_s[i] = a.b1[i];
-        if (tid < D) b2_s[tid] = a.b2[tid];
+    // the weight stream (workgroups past the row count have left without moving data): only the items of steps 0 and 1
+    // for now -- the x rows are still on their way and would be slowed down by more; the rest of the ring follows
+    // at the barrier below, which the computing waves reach once their loads have arrived
+    int last = 1;                                // newest item requested
+    if (loader) {
+        for (int q = 0; q <= last; ++q) issue_item(q);
+        // the rest of both matrices: into L2 now, so that the ring refills below are L2 hits
+        l2_warm(a.W1t, (long)Dm * D * 2, lds_addr_of(dump_s), tid - 256, 256);
+        l2_warm(a.W2t, (long)Dm * D * 2, lds_addr_of(dump_s), tid - 256, 256);
+    } else {
+        ln_gb_store<KT>(gbv, gb_s, tid);
+#pragma unroll
+        for (int j = 0; j < ML_MAX_DM / 256; ++j)
+            if (tid + 256 * j < Dm) b1_s[tid + 256 * j] = b1v[j];
+        if (tid < D) b2_s[tid] = b2v;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");    // gain and shift are in LDS
+    if (loader) {
+        for (int q = last + 1; q < min(ML_NS, NQ); ++q) issue_item(q);
+        last = min(ML_NS, NQ) - 1;
+    } else {
+        ln_finish<KT, 4>(xv, gb_s, a.eps, As, tid);
     }
     MLP_TS(3);
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -256,7 +278,7 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
 
 template <int KT> int launch_mlp_kt(const MlpArgs &a, hipStream_t st)
 {
-    constexpr int LDS = ((KT < 2 ? 2 : KT) + ML_NS * KT) * 64 * 64 * 2 + (ML_MAX_DM + 64 * KT + 64) * 4 + MLP_TS_BYTES;
+    constexpr int LDS = ((KT < 2 ? 2 : KT) + ML_NS * KT) * 64 * 64 * 2 + (ML_MAX_DM + 64 * KT + 64 + 128 * KT) * 4 + MLP_TS_BYTES;
     auto kern = mlp_kernel<KT>;
     if (LDS > 64 * 1024) {
         static bool attr_set = false;   // raising the dynamic LDS limit is a per-kernel, process-wide setting

@@ -54,21 +54,37 @@ template <int N> __device__ __forceinline__ void rl_wait_barrier()
 
 // LayerNorm (fp32 statistics) of the 64 rows t0 .. t0 + 63 of one block of fp32 rows with K = 64 * KT elements,
 // written as bf16 into KT swizzled [64][64] tiles at As.  64 * TPR threads (tid 0 .. 64 TPR - 1), TPR = 4 or 8 per
-// row, K / TPR contiguous elements each; gain and shift are requested together with the rows (one latency,
-// not two).  Rows past T repeat row T - 1: whatever is computed from them is never stored.
+// row.  A thread takes the 16-byte pieces part, part + TPR, part + 2 TPR, ... of its row, so that the TPR lanes of
+// a row read 16 TPR contiguous bytes per instruction (with one contiguous stretch per thread every lane of an
+// instruction would touch a cache line of its own).  Rows past T repeat row T - 1: whatever is computed from
+// them is never stored.  Two halves, so that the caller can put a barrier between them: ln_load requests the
+// rows; ln_finish reads gain and shift from LDS (gb_s: g[K] then b[K], staged by ln_gb_load / ln_gb_store before that
+// barrier -- fetching them from global memory per thread would triple the number of loads of the prologue).
 template <int KT, int TPR>
-__device__ __forceinline__ void ln_rows_to_lds(const float *xblock, int T, int t0, const float *ln_g, const float *ln_b, float eps,
-                                               bf16_t *As, int tid)
+__device__ __forceinline__ void ln_load(const float *xblock, int T, int t0, int tid, f32x4 (&v)[64 * KT / TPR / 4])
 {
-    constexpr int K = 64 * KT, PER = K / TPR, NV = PER / 4;
+    constexpr int K = 64 * KT, NV = K / TPR / 4;
     const int row = tid / TPR, part = tid % TPR;
-    const float *xr = xblock + (size_t)min(t0 + row, T - 1) * K + part * PER;
-    const float *gp = ln_g + part * PER, *bp = ln_b + part * PER;
-    f32x4 v[NV], gv[NV], bv[NV];
+    const float *xr = xblock + (size_t)min(t0 + row, T - 1) * K + 4 * part;
 #pragma unroll
-    for (int i = 0; i < NV; ++i) v[i] = *(const f32x4 *)(xr + 4 * i);
-#pragma unroll
-    for (int i = 0; i < NV; ++i) { gv[i] = *(const f32x4 *)(gp + 4 * i); bv[i] = *(const f32x4 *)(bp + 4 * i); }
+    for (int i = 0; i < NV; ++i) v[i] = *(const f32x4 *)(xr + 4 * TPR * i);
+}
+// gain and shift: requested by threads 0 .. K/2 - 1 (ln_gb_load, early), written to LDS later (ln_gb_store)
+template <int KT> __device__ __forceinline__ f32x4 ln_gb_load(const float *ln_g, const float *ln_b, int tid)
+{
+    constexpr int K = 64 * KT;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    return tid < K / 2 ? (tid < K / 4 ? *(const f32x4 *)(ln_g + 4 * tid) : *(const f32x4 *)(ln_b + 4 * (tid - K / 4))) : zero;
+}
+template <int KT> __device__ __forceinline__ void ln_gb_store(f32x4 v, float *gb_s, int tid)
+{
+    if (tid < 32 * KT) *(f32x4 *)(gb_s + 4 * tid) = v;
+}
+template <int KT, int TPR>
+__device__ __forceinline__ void ln_finish(const f32x4 (&v)[64 * KT / TPR / 4], const float *gb_s, float eps, bf16_t *As, int tid)
+{
+    constexpr int K = 64 * KT, NV = K / TPR / 4;
+    const int row = tid / TPR, part = tid % TPR;
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
@@ -84,14 +100,13 @@ __device__ __forceinline__ void ln_rows_to_lds(const float *xblock, int T, int t
     for (int m = 1; m < TPR; m <<= 1) q += __shfl_xor(q, m, 64);
     const float inv = rsqrtf(q * (1.0f / K) + eps);
 #pragma unroll
-    for (int c = 0; c < PER / 8; ++c) {
-        bf16x8 o;
+    for (int i = 0; i < NV; ++i) {
+        const int k = 4 * (TPR * i + part);          // first of this piece's 4 elements
+        const f32x4 g = *(const f32x4 *)(gb_s + k), b = *(const f32x4 *)(gb_s + K + k);
+        bf16x4 o;
 #pragma unroll
-        for (int z = 0; z < 4; ++z) {
-            o[z] = (bf16_t)((v[2 * c][z] - mean) * inv * gv[2 * c][z] + bv[2 * c][z]);
-            o[4 + z] = (bf16_t)((v[2 * c + 1][z] - mean) * inv * gv[2 * c + 1][z] + bv[2 * c + 1][z]);
-        }
-        const int k = part * PER + 8 * c;   // first of 8 consecutive k: tile k / 64, chunk (k % 64) / 8
-        *(bf16x8 *)(As + (k >> 6) * (64 * 64) + tile_off(row, (k & 63) >> 3)) = o;
+        for (int z = 0; z < 4; ++z) o[z] = (bf16_t)((v[i][z] - mean) * inv * g[z] + b[z]);
+        // tile k / 64, 16-byte chunk (k % 64) / 8, first or second half of it
+        *(bf16x4 *)(As + (k >> 6) * (64 * 64) + tile_off(row, (k & 63) >> 3) + (k & 4)) = o;
     }
 }

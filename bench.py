@@ -41,20 +41,32 @@ def gemm_launches(cfg, F, R, L0):
     """One entry per linear-kernel launch of a forward: the list of (rows, K, N, lora, lora_rows) products it computes."""
     T, D, Dm = cfg.T, cfg.D, cfg.Dm
     out = [[(F * (T - 1), cfg.patch_dim, D, False, 0)]]
+    narrow = D in (64, 128, 192) and Dm % 64 == 0 and 128 <= Dm <= 768
+    qkv_done = False
     for l in range(cfg.L):
         if l >= L0 and R == 0:
             break
         ad = l >= L0
         rows_qkv_in = (F if l <= L0 else R) * T      # the base product of the fan-out layer runs once per frame
         rows = (R if ad else F) * T
-        out.append([(rows_qkv_in, D, 3 * D, ad and cfg.targets & 1, rows)])
-        out.append([(rows, D, D, ad and cfg.targets & 2, rows)])
+        qkv = (rows_qkv_in, D, 3 * D, ad and cfg.targets & 1, rows)
+        proj = (rows, D, D, ad and cfg.targets & 2, rows)
         fc1 = (rows, D, Dm, ad and cfg.targets & 4, rows)
         fc2 = (rows, Dm, D, ad and cfg.targets & 8, rows)
-        if D in (64, 128, 192) and Dm % 128 == 0 and Dm <= 768 and not (fc1[3] or fc2[3]):
-            out.append([fc1, fc2])                   # one kernel for the whole MLP half
+        if not qkv_done:
+            out.append([qkv])
+        qkv_done = False
+        if narrow and not (fc1[3] or fc2[3]):
+            # one kernel for everything row-wise: proj, the MLP half and the next layer's qkv (same blocks only)
+            launch = [proj, fc1, fc2]
+            ln = l + 1
+            if ln < cfg.L and ln != L0:
+                adn = ln >= L0
+                launch.append(((R if adn else F) * T, D, 3 * D, adn and cfg.targets & 1, (R if adn else F) * T))
+                qkv_done = True
+            out.append(launch)
         else:
-            out += [[fc1], [fc2]]
+            out += [[proj], [fc1], [fc2]]
     return out
 
 
@@ -150,7 +162,7 @@ def main():
     assert g["launches"] == n_gemm * n_prof, (g, n_gemm)
     avg_ms = g["ms"] / g["launches"]
     achieved = flops / n_gemm / (avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "bf16 MFMA linears: rowlin_kernel (LN + shrink + base + expand: qkv, proj), mlp_kernel (LN + fc1 + GELU + fc2 + residual), gemm_bf16_dma_kernel (patch embedding)",
+    roofline = {"bound": "mfma", "kernel": "bf16 MFMA linears: rowlayer_kernel (proj + LoRA + residual, LN, fc1, GELU, fc2, residual, LN, next qkv + LoRA in one launch per layer), rowlin_kernel (first qkv), gemm_bf16_dma_kernel (patch embedding)",
                 "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": LINEAR_HBM_BYTES_PER_LAUNCH if args.L0 == 0 else None,

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpoly.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "rowops.hip", "select.hip", "profile.hip", "rowlin.hip", "mlp.hip"]
+SOURCES = ["api.hip", "gemm.hip", "attention.hip", "rowops.hip", "select.hip", "profile.hip", "rowlin.hip", "mlp.hip", "rowlayer.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 ops are kept out of the generated code on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

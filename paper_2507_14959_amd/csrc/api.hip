@@ -132,6 +132,7 @@ extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *b
         POLY_TRY(launch_gemm(g, dt, st));
     }
 
+    bool qkv_done = false;                     // the qkv linear of layer l was computed by layer l - 1's row kernel
     for (int l = 0; l < m->L; ++l) {
         const bool lora_on = l >= m->L0 && R > 0;
         if (l >= m->L0 && R == 0) break;
@@ -172,7 +173,9 @@ extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *b
         const void *Wfc1 = (const char *)base->fc1_w + es * (size_t)l * Dm * D;
 
         // ---- attention half
-        if (fused(0)) {
+        if (qkv_done) {
+            qkv_done = false;
+        } else if (fused(0)) {
             POLY_TRY(rowlin(0, x_in, base->ln1_g + (size_t)l * D, base->ln1_b + (size_t)l * D, nullptr, fan_map, Wqkv,
                             base->qkv_b + (size_t)l * 3 * D, 3 * D, EPI_STORE, w.qkv, nullptr, nullptr));
         } else {
@@ -190,6 +193,34 @@ extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *b
             POLY_TRY(launch_gemm(g, dt, st));
         }
         POLY_TRY(launch_attention(w.qkv, w.o, T, D, m->heads, n_out, n_out_dev, dt, st));
+        // narrow models without adapters on fc1 / fc2: everything row-wise of the layer in one launch -- proj with its
+        // residual, the MLP half, and the qkv linear of the next layer when that layer works on the same blocks
+        if (dt == POLY_BF16 && !use(2) && !use(3) && rowlayer_supported(D, Dm, (use(0) || use(1)) ? m->r : 0)) {
+            RowLayerArgs a = {};
+            a.T = T; a.D = D; a.Dm = Dm; a.n_out = n_out; a.n_out_dev = n_out_dev;
+            a.adapter_of_out = lora_on ? w.adapter_of_row : nullptr; a.r = m->r; a.scale = m->lora_scale; a.eps = m->ln_eps;
+            a.o = (const bf16_t *)w.o; a.Wpt = (const bf16_t *)Wproj; a.bp = base->proj_b + (size_t)l * D;
+            if (use(1)) { a.Apt = (const bf16_t *)lora_ptr(lora->At[1], 1, D, D, true); a.Bpt = (const bf16_t *)lora_ptr(lora->Bt[1], 1, D, D, false); }
+            a.res = x_in; a.res_block_of_out = fan_map;
+            a.ln2_g = base->ln2_g + (size_t)l * D; a.ln2_b = base->ln2_b + (size_t)l * D;
+            a.W1t = (const bf16_t *)Wfc1; a.b1 = base->fc1_b + (size_t)l * Dm;
+            a.W2t = (const bf16_t *)((const char *)base->fc2_w + es * (size_t)l * D * Dm); a.b2 = base->fc2_b + (size_t)l * D;
+            a.x_out = x_out;
+            const int ln = l + 1;              // next layer: same blocks unless it is the one where frames fan out
+            if (ln < m->L && ln != m->L0) {
+                a.lnq_g = base->ln1_g + (size_t)ln * D; a.lnq_b = base->ln1_b + (size_t)ln * D;
+                a.Wqt = (const bf16_t *)((const char *)base->qkv_w + es * (size_t)ln * 3 * D * D); a.bq = base->qkv_b + (size_t)ln * 3 * D;
+                if (ln >= m->L0 && R > 0 && (m->targets & 1)) {
+                    const size_t per_layer = (size_t)m->n_adapters * m->r * D;
+                    a.Aqt = (const bf16_t *)((const char *)lora->At[0] + es * per_layer * (size_t)(ln - m->L0));
+                    a.Bqt = (const bf16_t *)((const char *)lora->Bt[0] + es * per_layer * 3 * (size_t)(ln - m->L0));
+                }
+                a.qkv_out = (bf16_t *)w.qkv;
+                qkv_done = true;
+            }
+            POLY_TRY(launch_rowlayer(a, st));
+            continue;
+        }
         if (fused(1)) {
             POLY_TRY(rowlin(1, nullptr, nullptr, nullptr, w.o, nullptr, Wproj, base->proj_b + (size_t)l * D, D, EPI_RESID, x_out, x_in, fan_map));
         } else {

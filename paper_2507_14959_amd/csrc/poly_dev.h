@@ -171,6 +171,41 @@ struct MlpArgs {
 };
 bool mlp_supported(int D, int Dm);
 int launch_mlp(const MlpArgs &a, hipStream_t st);
+
+// The row-wise part of a layer in one launch (rowlayer.hip):
+//   A (if o != null)        x' = res + o Wp + bp + scale (o Ap_k) Bp_k,  else x' = x_out
+//   B                       x_out = x' + GELU(LayerNorm2(x') W1 + b1) W2 + b2
+//   C (if qkv_out != null)  qkv_out = LayerNorm1'(x_out) Wq + bq + scale (.. Aq_k) Bq_k     (the next layer's qkv)
+// bf16 weights stored contraction-fastest, adapter stacks indexed by adapter_of_out[block]
+struct RowLayerArgs {
+    int T, D, Dm, n_out;
+    const int *n_out_dev;            // optional device-side block count (the smaller of the two is used)
+    const int *adapter_of_out;       // [n_out] or null
+    int r;
+    float scale, eps;
+    // A
+    const bf16_t *o;                 // [n_out][T][D]
+    const bf16_t *Wpt;               // [D][D]
+    const float *bp;                 // [D]
+    const bf16_t *Apt, *Bpt;         // [n_adapters][r][D], [n_adapters][D][r]; null = no adapters on proj
+    const float *res;                // [..][T][D] fp32 residual stream going in
+    const int *res_block_of_out;     // null = same block
+    // B
+    const float *ln2_g, *ln2_b;      // [D]
+    const bf16_t *W1t;               // [Dm][D]
+    const float *b1;                 // [Dm]
+    const bf16_t *W2t;               // [D][Dm]
+    const float *b2;                 // [D]
+    float *x_out;                    // [n_out][T][D] fp32 residual stream going out (may be the same buffer as res)
+    // C
+    const float *lnq_g, *lnq_b;      // [D]
+    const bf16_t *Wqt;               // [3 D][D]
+    const float *bq;                 // [3 D]
+    const bf16_t *Aqt, *Bqt;         // [n_adapters][r][D], [n_adapters][3 D][r]; null = no adapters on qkv
+    bf16_t *qkv_out;                 // [n_out][T][3 D]
+};
+bool rowlayer_supported(int D, int Dm, int r);
+int launch_rowlayer(const RowLayerArgs &a, hipStream_t st);
 int launch_rowlin(const RowLinArgs &a, hipStream_t st);
 
 // y = LayerNorm(x) row-wise; x float [n*T][D] -> elt [n*T][D]

@@ -1,0 +1,540 @@
+// Everything of a pre-LN transformer layer that works row by row, for narrow models (D <= 192), in one kernel
+// on tiles of 64 token rows:
+//
+//   A (optional)  x' = res + o Wp + bp + s (o Ap_k) Bp_k                 attention output projection, Sec. 3.1 form
+//   B             x'' = x' + GELU(LayerNorm2(x') W1 + b1) W2 + b2        feed-forward block (no low-rank branch here)
+//   C (optional)  qkv = LayerNorm1'(x'') Wq + bq + s (.. Aq_k) Bq_k      qkv linear of the NEXT layer
+//
+// Only softmax attention needs whole blocks; with A, B and C in one launch a layer is two kernels instead of
+// four, and x', the hidden activation and LayerNorm outputs never leave the chip.  Launch overhead and the cold
+// start of every kernel (inputs written by the previous kernel come from HBM) were a quarter of the layer time.
+//
+// Eight waves with two jobs, as in rowlin.hip / mlp.hip (a wave that issues a load into the saturated L2 path is
+// held at the issue stage, so the waves that compute issue none while they compute):
+//   waves 0-3 (2 x 2 over a 64 x 64 chunk): all MFMA work and the GELU;
+//   waves 4-7: the weight stream into a five-stage LDS ring (24 KB items), At_k / Bt_k of the block's adapter
+//             into LDS, and the residual stream: they hold x' (fp32, 4 threads per row) in registers from phase
+//             A to the end, do both LayerNorms on it and write x'' .
+// Phase boundaries pass a 64 x D fp32 tile through LDS (compute -> loaders); it takes the place of ring stages
+// 0-2, so every phase's stream starts in stage 3 and only two items of the next phase are prefetched across a
+// boundary.
+#include "poly_dev.h"
+#include "rowtile.h"
+
+#include <type_traits>
+
+namespace {
+
+constexpr int LY_NS = 5;            // LDS stages of the weight stream
+constexpr int LY_THREADS = 512;
+constexpr int LY_MAX_DM = 768;
+constexpr int LY_MAX_NQ = 576;      // qkv columns: 9 chunks, their accumulators stay in registers
+constexpr int LY_MAXCH = LY_MAX_NQ / 64;
+constexpr int LY_AT_STRIDE = 200;   // elements per rank row of At_k in LDS (192 + 8: rows start 4 banks apart)
+
+template <int KT, bool HAS_PROJ, bool HAS_QKV>
+__global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs a)
+{
+    constexpr int D = 64 * KT;
+    constexpr int A_EL = (KT < 2 ? 2 : KT) * 64 * 64;   // activation rows (KT tiles of [64][64]) / Bt_k / the two hidden tiles
+    constexpr int IT_EL = KT * 64 * 64;          // one stream item: KT tiles of [64][64]
+    constexpr int NLD = 2 * KT;                  // loads per loader wave and item: 16 rows of each tile, 8 rows per load
+    constexpr int NV = D / 16;                   // 16-byte pieces of an fp32 row per loader thread (4 threads per row)
+    constexpr int XSTRIDE = D * 4 + 16;          // bytes per row of the fp32 hand-over tile
+    extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
+    bf16_t *As = lds, *Ws = lds + A_EL;
+    float *b1_s = (float *)(lds + A_EL + LY_NS * IT_EL);   // [Dm]
+    float *bias_s = b1_s + LY_MAX_DM;                      // [D] bp in phase A, [3 D] bq in phase C
+    float *b2_s = bias_s + LY_MAX_NQ;                      // [D]
+    float *gb2_s = b2_s + D;                               // LayerNorm2 gain [D], shift [D]
+    float *gbq_s = gb2_s + 2 * D;                          // LayerNorm1' gain, shift
+    float *dump_s = gbq_s + 2 * D;                         // 64 words nobody reads (L2 warm-up loads)
+    bf16_t *at_s = (bf16_t *)(dump_s + 64);                // At_k of the current phase: [16][LY_AT_STRIDE]
+
+    const int tiles = (a.T + 63) / 64;
+    const int ob = blockIdx.x / tiles, t0 = (blockIdx.x % tiles) * 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool loader = wave >= 4;
+    const int wr = (wave >> 1) & 1, wc = wave & 1, lm = lane & 31, lh = lane >> 5;
+    const int lw = wave & 3, lr = lane >> 3, lt = tid & 255;
+    const int Dm = a.Dm, nch = Dm >> 6, NQ = 2 * nch;
+    const int Nq = 3 * D, nchq = (Nq + 63) / 64;
+    const int rows = min(64, a.T - t0);
+
+    // ---- the stream: positions in the ring.  Phase A: Wp chunk c at position c.  Phase B: item j at PB + j, in order
+    // of use (step h needs W2's slice of chunk h - 2 and W1's rows of chunk h):
+    //   j = 0, 1: W1(0), W1(1);  j = 2, 3: W2(0), W1(2);  j = 4, 5: W2(1), W1(3); ... ; last two: W2(nch-2), W2(nch-1).
+    // Phase C: Wq chunk c at PC + c.  Stage = position % 5; PB and PC are 3 mod 5 (see the head of this file).
+    const int NA = HAS_PROJ ? KT : 0;
+    const int PB = HAS_PROJ ? 3 : 0;
+    const int PC = HAS_QKV ? ((PB + NQ + 1) / 5) * 5 + 3 : 0;       // smallest position >= PB + NQ that is 3 mod 5
+    const int NI = NA + NQ + (HAS_QKV ? nchq : 0);                  // items, numbered in order
+    auto pos_of = [&](int i) { return i < NA ? i : (i < NA + NQ ? PB + (i - NA) : PC + (i - NA - NQ)); };
+    // loader wave w loads rows 16w .. 16w + 15 of each of the item's KT tiles, 8 rows (1 KB) per load; a row's 128 bytes
+    // land in lane order, the tile swizzle is applied by permuting the 16-byte pieces on the global side
+    auto issue_item = [&](int i) {
+        bf16_t *st = Ws + (pos_of(i) % LY_NS) * IT_EL;
+        const bf16_t *base;
+        int rstride, tstride, nrow;                       // elements between rows / between tiles; rows that exist
+        if (i < NA) { base = a.Wpt + (size_t)i * 64 * D; rstride = D; tstride = 64; nrow = D - i * 64; }
+        else if (i < NA + NQ) {
+            const int q = i - NA;
+            const bool second = q >= 2 && ((q & 1) == 0 || q == NQ - 1);
+            const int c = q < 2 ? q : (second ? (q == NQ - 1 ? nch - 1 : (q >> 1) - 1) : (q + 1) >> 1);
+            if (!second) { base = a.W1t + (size_t)c * 64 * D; rstride = D; tstride = 64; }              // tile t: k = 64 t ..
+            else { base = a.W2t + (size_t)c * 64; rstride = Dm; tstride = 64 * Dm; }                      // tile t: output columns 64 t ..
+            nrow = 64;
+        } else { const int c = i - NA - NQ; base = a.Wqt + (size_t)c * 64 * D; rstride = D; tstride = 64; nrow = Nq - c * 64; }
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int row = lw * 16 + half * 8 + lr;
+            const unsigned off = (min(row, nrow - 1) * rstride + (((lane & 7) ^ ((row >> 1) & 7)) << 3)) * 2;   // rows past the matrix repeat its last row
+#pragma unroll
+            for (int t = 0; t < KT; ++t)
+                glds16_s(base + (size_t)t * tstride, off, __builtin_amdgcn_readfirstlane(lds_addr_of(st + t * 4096 + (lw * 16 + half * 8) * 64)));
+        }
+    };
+    // At_k [r][D] -> at_s, one rank row per load (24 * KT / 3 lanes), rows LY_AT_STRIDE elements apart
+    auto issue_at = [&](const bf16_t *At_k, int r) {
+        for (int rk = lw; rk < r; rk += 4)
+            if (lane < D / 8) glds16(At_k + (size_t)rk * D + lane * 8, __builtin_amdgcn_readfirstlane(lds_addr_of(at_s + rk * LY_AT_STRIDE)));
+    };
+    // Bt_k [N][r] -> As, as it is
+    auto issue_bt = [&](const bf16_t *Bt_k, int N, int r) {
+        const int n16 = (N * r) >> 3;
+        for (int i0 = lw * 64; i0 < n16; i0 += 256)
+            if (i0 + lane < n16) glds16((const char *)Bt_k + (size_t)(i0 + lane) * 16, __builtin_amdgcn_readfirstlane(lds_addr_of(As) + i0 * 16));
+    };
+
+    // ---- everything whose address needs no metadata is requested first: it comes from HBM (another kernel has just
+    // written it), and whatever is requested first is served first
+    bf16x8 pv[D / 32];                           // computing waves: o rows (4 threads per row, pieces part, part + 4, ..)
+    f32x4 xr[NV];                                // loader waves: residual rows, then x', then x''
+    f32x4 gb2v = {0.f, 0.f, 0.f, 0.f}, gbqv = {0.f, 0.f, 0.f, 0.f};
+    float b1v[LY_MAX_DM / 256], bqv[(LY_MAX_NQ + 255) / 256], b2v = 0.f, bpv = 0.f;
+    const bool res_early = !HAS_PROJ || a.res_block_of_out == nullptr;
+    auto load_res = [&](int rblk) {
+        const float *src = (HAS_PROJ ? a.res : a.x_out) + ((size_t)rblk * a.T + min(t0 + (lt >> 2), a.T - 1)) * D + 4 * (lt & 3);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) xr[i] = *(const f32x4 *)(src + 16 * i);
+    };
+    if (!loader) {
+        if (HAS_PROJ) {
+            const bf16_t *src = a.o + ((size_t)ob * a.T + min(t0 + (tid >> 2), a.T - 1)) * D + 8 * (tid & 3);
+#pragma unroll
+            for (int i = 0; i < D / 32; ++i) pv[i] = *(const bf16x8 *)(src + 32 * i);
+            if (tid < D) bpv = a.bp[tid];
+        }
+        gb2v = ln_gb_load<KT>(a.ln2_g, a.ln2_b, tid);
+#pragma unroll
+        for (int j = 0; j < LY_MAX_DM / 256; ++j) b1v[j] = tid + 256 * j < Dm ? a.b1[tid + 256 * j] : 0.f;
+        if (tid < D) b2v = a.b2[tid];
+        if (HAS_QKV) {
+            gbqv = ln_gb_load<KT>(a.lnq_g, a.lnq_b, tid);
+#pragma unroll
+            for (int j = 0; j < (LY_MAX_NQ + 255) / 256; ++j) bqv[j] = tid + 256 * j < Nq ? a.bq[tid + 256 * j] : 0.f;
+        }
+    } else if (res_early) {
+        load_res(ob);
+    }
+
+    const int n_out = a.n_out_dev ? min(*a.n_out_dev, a.n_out) : a.n_out;
+    if (ob >= n_out) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        return;
+    }
+    const int k_ad = a.adapter_of_out ? a.adapter_of_out[ob] : -1;
+    const bool lora_p = HAS_PROJ && a.Apt && k_ad >= 0, lora_q = HAS_QKV && a.Aqt && k_ad >= 0;
+
+    // ---- loader bookkeeping.  last: newest item requested; cpos: newest ring position every wave is done with.
+    // An item may be requested once the item five positions earlier has been consumed, and never beyond `cap`
+    // (the positions that a hand-over tile is about to use).
+    int last = -1;
+    auto refill = [&](int cpos, int cap) {
+        while (last + 1 < NI && pos_of(last + 1) <= min(cpos + LY_NS, cap)) issue_item(++last);
+    };
+    auto wait_item = [&](int need) {             // item `need` has landed; newer ones may stay in flight (loads complete in issue order)
+        const int ahead = last - need;
+        if (ahead >= 3) rl_wait_barrier<3 * NLD>();
+        else if (ahead == 2) rl_wait_barrier<2 * NLD>();
+        else if (ahead == 1) rl_wait_barrier<NLD>();
+        else rl_wait_barrier<0>();
+    };
+    const int capA = PB + 1, capB = HAS_QKV ? PC + 1 : 1 << 30;   // stages 0-2 are kept free for the tile at the end of A / B
+
+    if (loader) {
+        if (!res_early) load_res(a.res_block_of_out[ob]);
+        // only two items for now -- the rows above are still on their way and would be slowed down by more
+        // (At_k first: the wait for the first chunks then covers it -- loads complete in issue order)
+        if (lora_p) issue_at(a.Apt + (size_t)k_ad * a.r * D, a.r);
+        refill(-1, 1);
+        l2_warm(a.W1t, (long)Dm * D * 2, lds_addr_of(dump_s), lt, 256);
+        l2_warm(a.W2t, (long)Dm * D * 2, lds_addr_of(dump_s), lt, 256);
+    } else {
+        // prologue of the computing waves: what they requested -> LDS
+        if (HAS_PROJ) {
+#pragma unroll
+            for (int i = 0; i < D / 32; ++i) {
+                const int k = 8 * (4 * i + (tid & 3));
+                *(bf16x8 *)(As + (k >> 6) * 4096 + tile_off(tid >> 2, (k & 63) >> 3)) = pv[i];
+            }
+            if (tid < D) bias_s[tid] = bpv;
+        }
+        ln_gb_store<KT>(gb2v, gb2_s, tid);
+        if (HAS_QKV) ln_gb_store<KT>(gbqv, gbq_s, tid);
+#pragma unroll
+        for (int j = 0; j < LY_MAX_DM / 256; ++j)
+            if (tid + 256 * j < Dm) b1_s[tid + 256 * j] = b1v[j];
+        if (tid < D) b2_s[tid] = b2v;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // B0: o rows, biases, gains are in LDS
+
+    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    const bf16x4 zero4 = {0, 0, 0, 0};
+    bf16x8 fa[KT * 4];                           // the resident rows wr*32 + lm as the B operand of the transposed product
+    auto load_fa = [&]() {
+#pragma unroll
+        for (int kk = 0; kk < KT * 4; ++kk)
+            fa[kk] = *(const bf16x8 *)(As + (kk >> 2) * 4096 + tile_off(wr * 32 + lm, 2 * (kk & 3) + lh));
+    };
+    // shrink: c[n][m] = sum_k At[n][k] x[m][k] with At_k from at_s; lane (lm, lh) ends up with ranks 4*lh + {0..3} (c[0..3])
+    // and 8 + 4*lh + {0..3} (c[4..7]) of row lm -- exactly the 8 contraction slots it must supply to the expand
+    auto shrink = [&](int r) {
+        f32x16 c;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) c[e] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KT * 4; ++kk) {
+            const bf16x8 ft = lm < r ? *(const bf16x8 *)(at_s + min(lm, 15) * LY_AT_STRIDE + kk * 16 + lh * 8) : zero8;
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ft, fa[kk], c, 0, 0, 0);
+        }
+        bf16x8 fs;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) fs[j] = (bf16_t)(a.scale * c[j]);
+        return fs;
+    };
+    // expand operand of output column n from Bt_k (in As): ranks 4*lh + {0..3} and 8 + 4*lh + {0..3}; r is a multiple of 4:
+    // each half is one 8-byte read at a clamped offset, zeroed where the rank does not exist
+    auto bt_frag = [&](int n, int r) {
+        const bool lo_ok = 4 * lh + 4 <= r, hi_ok = 8 + 4 * lh + 4 <= r;
+        const bf16_t *bt = As + (size_t)n * r;
+        const bf16x4 lo = lo_ok ? *(const bf16x4 *)(bt + 4 * lh) : zero4, hi = hi_ok ? *(const bf16x4 *)(bt + 8 + 4 * lh) : zero4;
+        return bf16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    };
+    // one or two chunks of a plain linear against the resident rows: acc starts from the bias; operands are fetched one
+    // K step (16) ahead of the MFMAs that use them (LDS latency is a hundred-odd cycles, and the compiler on its own
+    // keeps only two or three reads in flight)
+    auto linear_step = [&](f32x16 &acc0, f32x16 &acc1, int c0, int pos0, int N, auto PAIR) {
+        constexpr bool pair = decltype(PAIR)::value;
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        const bf16_t *st0 = Ws + (pos0 % LY_NS) * IT_EL, *st1 = Ws + ((pos0 + 1) % LY_NS) * IT_EL;
+        bf16x8 fw0[2][KT], fw1[2][KT];
+        auto load = [&](int kk, int sl) {
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt) {
+                fw0[sl][kt] = *(const bf16x8 *)(st0 + kt * 4096 + tile_off(wc * 32 + lm, 2 * kk + lh));
+                if (pair) fw1[sl][kt] = *(const bf16x8 *)(st1 + kt * 4096 + tile_off(wc * 32 + lm, 2 * kk + lh));
+            }
+        };
+        load(0, 0);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 b0 = *(const f32x4 *)(bias_s + min(c0 * 64 + wc * 32 + 8 * g + 4 * lh, N - 4));
+#pragma unroll
+            for (int z = 0; z < 4; ++z) acc0[4 * g + z] = b0[z];
+            if (pair) {
+                const f32x4 b1 = *(const f32x4 *)(bias_s + min((c0 + 1) * 64 + wc * 32 + 8 * g + 4 * lh, N - 4));
+#pragma unroll
+                for (int z = 0; z < 4; ++z) acc1[4 * g + z] = b1[z];
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk < 3) load(kk + 1, (kk + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt) {
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw0[kk & 1][kt], fa[kt * 4 + kk], acc0, 0, 0, 0);
+                if (pair) acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw1[kk & 1][kt], fa[kt * 4 + kk], acc1, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // loaders: x' (or x'') rows in xr -> LayerNorm -> As, gains from gb_s (the same 4-threads-per-row split as ln_finish)
+    char *xtile = (char *)Ws;                    // the fp32 hand-over tile: ring stages 0-2
+
+    // ================================================================ phase A: x' = res + o Wp + bp + lora
+    if (HAS_PROJ) {
+        constexpr int SA = (KT + 1) / 2;
+        if (loader) {
+            refill(-1, capA);
+            for (int s = 0; s < SA; ++s) {
+                wait_item(min(2 * s + 1, KT - 1));
+                if (s == 0 && lora_p) issue_bt(a.Bpt + (size_t)k_ad * D * a.r, D, a.r);     // the computing waves hold their fragments by now
+                refill(2 * s - 1, capA);
+            }
+            rl_wait_barrier<0>();                                               // Bf: Bt_k has landed
+            asm volatile("s_barrier" ::: "memory");                             // Bs: the tile is complete
+#pragma unroll
+            for (int i = 0; i < NV; ++i) xr[i] += *(const f32x4 *)(xtile + (lt >> 2) * XSTRIDE + (4 * i + (lt & 3)) * 16);
+            ln_finish<KT, 4>(xr, gb2_s, a.eps, As, lt);
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bl: LayerNorm2(x') is in As, the tile is dead
+            refill(PB - 1, capB);
+        } else {
+            load_fa();
+            f32x16 accp[KT + 1];
+#pragma unroll
+            for (int s = 0; s < SA; ++s) {
+                if (2 * s + 1 < KT) linear_step(accp[2 * s], accp[2 * s + 1], 2 * s, 2 * s, D, std::true_type{});
+                else linear_step(accp[2 * s], accp[2 * s], 2 * s, 2 * s, D, std::false_type{});
+            }
+            bf16x8 fs = zero8;
+            if (lora_p) fs = shrink(a.r);                                       // At_k landed before the first chunk did
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bf
+            if (lora_p) {
+#pragma unroll
+                for (int c = 0; c < KT; ++c) accp[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bt_frag(c * 64 + wc * 32 + lm, a.r), fs, accp[c], 0, 0, 0);
+            }
+            // the ring positions 0 .. KT - 1 are consumed: the tile takes stages 0-2
+            char *trow = xtile + (wr * 32 + lm) * XSTRIDE + (wc * 32 + 4 * lh) * 4;
+#pragma unroll
+            for (int c = 0; c < KT; ++c)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *(f32x4 *)(trow + (c * 64 + 8 * g) * 4) = f32x4{accp[c][4 * g], accp[c][4 * g + 1], accp[c][4 * g + 2], accp[c][4 * g + 3]};
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bs
+            asm volatile("s_barrier" ::: "memory");                             // Bl
+        }
+    } else {
+        if (loader) {
+            ln_finish<KT, 4>(xr, gb2_s, a.eps, As, lt);
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bl: LayerNorm2(x') is in As
+            refill(PB - 1, capB);
+        } else {
+            asm volatile("s_barrier" ::: "memory");                             // Bl
+        }
+    }
+
+    // ================================================================ phase B: y = GELU(LayerNorm2(x') W1 + b1) W2
+    f32x16 y[KT];                                // rows wr*32 + lm, columns wc*32*KT + 32 p + ..
+    if (loader) {
+        auto need_at = [&](int h) { return h < 2 ? h : min(2 * h - 1, NQ - 1); };
+        for (int h = 0; h < nch + 2; ++h) {
+            wait_item(NA + need_at(h));
+            refill(h >= 1 ? PB + need_at(h - 1) : PB - 1, capB);
+        }
+        rl_wait_barrier<0>();                                                   // Be: every item of B is consumed
+        if (lora_q) issue_at(a.Aqt + (size_t)k_ad * a.r * D, a.r);              // before the chunks of C, whose wait then covers it
+        refill(HAS_QKV ? PC - 1 : 0, HAS_QKV ? PC + 1 : -1);                    // (the tile still needs stages 0-2)
+        asm volatile("s_barrier" ::: "memory");                                 // By: the y tile is complete
+        float *dst = a.x_out + ((size_t)ob * a.T + t0 + (lt >> 2)) * D + 4 * (lt & 3);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            xr[i] += *(const f32x4 *)(xtile + (lt >> 2) * XSTRIDE + (4 * i + (lt & 3)) * 16) + *(const f32x4 *)(b2_s + 4 * (4 * i + (lt & 3)));
+            if ((lt >> 2) < rows) *(f32x4 *)(dst + 16 * i) = xr[i];
+        }
+        if (HAS_QKV) ln_finish<KT, 4>(xr, gbq_s, a.eps, As, lt);
+    } else {
+        load_fa();
+        f32x16 hcur, hnext;                      // first product of chunks h - 1 / h: row lm, columns wc*32 + 8*(e/4) + 4*lh + e%4
+#pragma unroll
+        for (int p = 0; p < KT; ++p)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) y[p][e] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) hcur[e] = hnext[e] = 0.f;
+        bf16_t *Hs = As;                         // hidden tiles [64 rows][64 columns of a chunk], chunk c in tile c & 1 (As is dead
+                                                 // once every wave has its fa: the barrier of step 0 comes before the first write)
+        // step h: d1: hnext = LayerNorm2(x') W1 rows of chunk h; dg: hidden tile of chunk h - 1 = GELU(hcur + b1);
+        // d2: y += hidden(chunk h - 2) W2 slice, with a quarter of the GELU arithmetic between the MFMAs of each K step
+        auto compute_step = [&](auto D1, auto DG, auto D2, int h) {
+            constexpr bool d1 = decltype(D1)::value, dg = decltype(DG)::value, d2 = decltype(D2)::value;
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            const bf16_t *s2 = Ws + ((PB + (h == nch + 1 ? NQ - 1 : 2 * h - 2)) % LY_NS) * IT_EL;   // W2(h - 2)
+            const bf16_t *s1 = Ws + ((PB + (h < 2 ? h : 2 * h - 1)) % LY_NS) * IT_EL;               // W1(h)
+            const bf16_t *Hr = Hs + (h & 1) * 4096;                                                  // chunk h - 2
+            bf16_t *Hw = Hs + ((h - 1) & 1) * 4096;                                                  // chunk h - 1
+            bf16x8 fh[2], f2[2][KT], f1[2][KT];
+            f32x4 b[4];
+            auto load = [&](int kk, int s) {
+                if (d2) {
+                    fh[s] = *(const bf16x8 *)(Hr + tile_off(wr * 32 + lm, 2 * kk + lh));
+#pragma unroll
+                    for (int p = 0; p < KT; ++p) {
+                        const int ncol = wc * 32 * KT + p * 32;   // first of this piece's 32 output columns
+                        f2[s][p] = *(const bf16x8 *)(s2 + (ncol >> 6) * 4096 + tile_off((ncol & 63) + lm, 2 * kk + lh));
+                    }
+                }
+                if (d1) {
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt) f1[s][kt] = *(const bf16x8 *)(s1 + kt * 4096 + tile_off(wc * 32 + lm, 2 * kk + lh));
+                }
+            };
+            if (dg) {
+                const float *bp = b1_s + (h - 1) * 64 + wc * 32 + 4 * lh;
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) b[g4] = *(const f32x4 *)(bp + 8 * g4);
+            }
+            load(0, 0);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                if (kk < 3) load(kk + 1, (kk + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (d2) {
+#pragma unroll
+                    for (int p = 0; p < KT; ++p) y[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[kk & 1][p], fh[kk & 1], y[p], 0, 0, 0);
+                }
+                if (d1) {
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt) hnext = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[kk & 1][kt], fa[kt * 4 + kk], hnext, 0, 0, 0);
+                }
+                if (dg) {
+                    const f32x4 v = gelu_poly4(f32x4{hcur[4 * kk], hcur[4 * kk + 1], hcur[4 * kk + 2], hcur[4 * kk + 3]} + b[kk]);
+                    const bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+                    *(bf16x4 *)(Hw + tile_off(wr * 32 + lm, 4 * wc + kk) + 4 * lh) = o;
+                }
+                if ((d1 || d2) && dg) {
+                    // one MFMA, then a share of the vector work, so that the vector work is issued while an MFMA runs
+                    constexpr int NM = (d1 ? KT : 0) + (d2 ? KT : 0);
+#pragma unroll
+                    for (int i = 0; i < NM; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, (64 + NM - 1) / NM, 0);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (d1) {
+                hcur = hnext;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) hnext[e] = 0.f;
+            }
+        };
+        using T_ = std::true_type;
+        using F_ = std::false_type;
+        compute_step(T_{}, F_{}, F_{}, 0);
+        compute_step(T_{}, T_{}, F_{}, 1);
+        for (int h = 2; h < nch; ++h) compute_step(T_{}, T_{}, T_{}, h);
+        compute_step(F_{}, T_{}, T_{}, nch);
+        compute_step(F_{}, F_{}, T_{}, nch + 1);
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // Be: the ring positions of B are consumed
+        char *trow = xtile + (wr * 32 + lm) * XSTRIDE + (wc * 32 * KT + 4 * lh) * 4;
+#pragma unroll
+        for (int p = 0; p < KT; ++p)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4)
+                *(f32x4 *)(trow + (p * 32 + 8 * g4) * 4) = f32x4{y[p][4 * g4], y[p][4 * g4 + 1], y[p][4 * g4 + 2], y[p][4 * g4 + 3]};
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // By
+        if (HAS_QKV) {
+#pragma unroll
+            for (int j = 0; j < (LY_MAX_NQ + 255) / 256; ++j)
+                if (tid + 256 * j < Nq) bias_s[tid + 256 * j] = bqv[j];
+        }
+    }
+    if (!HAS_QKV) return;
+
+    // ================================================================ phase C: qkv = LayerNorm1'(x'') Wq + bq + lora
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");             // Bz: LayerNorm1'(x'') is in As, bq in LDS, the tile is dead
+    f32x16 acc[LY_MAXCH + 1];                    // acc[c][e]: row wr*32 + lm, column c*64 + wc*32 + 8*(e/4) + 4*lh + e%4
+    const int i0q = NA + NQ;                     // first item of C
+    if (loader) {
+        refill(PC - 1, 1 << 30);
+        for (int s = 0; 2 * s < nchq; ++s) {
+            wait_item(i0q + min(2 * s + 1, nchq - 1));
+            if (s == 0 && lora_q) issue_bt(a.Bqt + (size_t)k_ad * Nq * a.r, Nq, a.r);   // the computing waves hold their fragments by now
+            refill(PC + 2 * s - 1, 1 << 30);
+        }
+        rl_wait_barrier<0>();                                                   // Bf2: Bt_k has landed; the ring is dead
+        asm volatile("s_barrier" ::: "memory");                                 // Bg2: expand done, Bt_k is dead
+    } else {
+        load_fa();
+#pragma unroll
+        for (int s = 0; s < (LY_MAXCH + 1) / 2; ++s) {
+            // uniform conditions, written as guards (not a break) so that the loop unrolls and acc stays in registers
+            if (2 * s + 1 < nchq) linear_step(acc[2 * s], acc[2 * s + 1], 2 * s, PC + 2 * s, Nq, std::true_type{});
+            else if (2 * s < nchq) linear_step(acc[2 * s], acc[2 * s], 2 * s, PC + 2 * s, Nq, std::false_type{});
+        }
+        bf16x8 fs = zero8;
+        if (lora_q) fs = shrink(a.r);                                           // At_k landed before the first chunk did
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // Bf2
+        if (lora_q) {
+#pragma unroll
+            for (int c = 0; c < LY_MAXCH; ++c)
+                if (c < nchq) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bt_frag(min(c * 64 + wc * 32 + lm, Nq - 1), a.r), fs, acc[c], 0, 0, 0);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // Bg2
+        // A lane owns one row, so storing from registers would touch 32 cache lines per instruction with 8 bytes each:
+        // the finished bf16 tile is laid out row-major in LDS and copied out in 16-byte pieces of consecutive threads
+        const int qstride = ((Nq * 2 + 255) & ~255) + 16;
+        char *trow = (char *)lds + (wr * 32 + lm) * qstride + (wc * 32 + 4 * lh) * 2;
+#pragma unroll
+        for (int c = 0; c < LY_MAXCH; ++c) {
+            if (c < nchq) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const bf16x4 w = {(bf16_t)acc[c][4 * g], (bf16_t)acc[c][4 * g + 1], (bf16_t)acc[c][4 * g + 2], (bf16_t)acc[c][4 * g + 3]};
+                    if ((c + 1) * 64 <= Nq || c * 64 + wc * 32 + 8 * g + 4 * lh < Nq) *(bf16x4 *)(trow + (c * 64 + 8 * g) * 2) = w;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    {
+        const int qstride = ((Nq * 2 + 255) & ~255) + 16, pieces = (Nq * 2) >> 4;
+        char *out = (char *)a.qkv_out + ((size_t)ob * a.T + t0) * Nq * 2;
+        for (int idx = tid; idx < rows * pieces; idx += LY_THREADS) {
+            const int row = idx / pieces, p = idx - row * pieces;
+            *(f32x4 *)(out + (size_t)row * Nq * 2 + p * 16) = *(const f32x4 *)((const char *)lds + row * qstride + p * 16);
+        }
+    }
+}
+
+template <int KT, bool HAS_PROJ, bool HAS_QKV> int launch_layer_t(const RowLayerArgs &a, hipStream_t st)
+{
+    constexpr int D = 64 * KT;
+    constexpr int LDS = ((KT < 2 ? 2 : KT) + LY_NS * KT) * 64 * 64 * 2 + (LY_MAX_DM + LY_MAX_NQ + D + 4 * D + 64) * 4 + 16 * LY_AT_STRIDE * 2;
+    static_assert(LDS <= 160 * 1024, "LDS budget");
+    auto kern = rowlayer_kernel<KT, HAS_PROJ, HAS_QKV>;
+    if (LDS > 64 * 1024) {
+        static bool attr_set = false;   // raising the dynamic LDS limit is a per-kernel, process-wide setting
+        if (!attr_set) {
+            if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess) return POLY_EHIP;
+            attr_set = true;
+        }
+    }
+    const int tiles = (a.T + 63) / 64;
+    POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, kern, dim3((unsigned)(a.n_out * tiles)), dim3(LY_THREADS), LDS, st, a);
+    return hipGetLastError() == hipSuccess ? POLY_OK : POLY_EHIP;
+}
+
+template <int KT> int launch_layer_kt(const RowLayerArgs &a, hipStream_t st)
+{
+    const bool p = a.o != nullptr, q = a.qkv_out != nullptr;
+    if (p && q) return launch_layer_t<KT, true, true>(a, st);
+    if (p) return launch_layer_t<KT, true, false>(a, st);
+    if (q) return launch_layer_t<KT, false, true>(a, st);
+    return launch_layer_t<KT, false, false>(a, st);
+}
+
+}  // namespace
+
+// D, Dm: model and hidden width; r: adapter rank of the proj / qkv linears that carry adapters (0 = none)
+bool rowlayer_supported(int D, int Dm, int r)
+{
+    if (!((D == 64 || D == 128 || D == 192) && Dm >= 128 && Dm % 64 == 0 && Dm <= LY_MAX_DM)) return false;
+    if (r != 0 && !(r >= 4 && r <= 16 && r % 4 == 0)) return false;
+    // Bt_k of the qkv linear [3 D][r] takes the place of the activation rows
+    return (long)3 * D * r * 2 <= (long)(D / 64 < 2 ? 2 : D / 64) * 64 * 64 * 2;
+}
+
+int launch_rowlayer(const RowLayerArgs &a, hipStream_t st)
+{
+    if (a.n_out <= 0 || a.T <= 0) return POLY_OK;
+    const bool lora = (a.o && a.Apt) || (a.qkv_out && a.Aqt);
+    if (!rowlayer_supported(a.D, a.Dm, lora ? a.r : 0)) return POLY_EINVAL;
+    switch (a.D / 64) {
+    case 1: return launch_layer_kt<1>(a, st);
+    case 2: return launch_layer_kt<2>(a, st);
+    default: return launch_layer_kt<3>(a, st);
+    }
+}

@@ -122,8 +122,8 @@ extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *b
     POLY_TRY(launch_prep(row_offsets, adapter_ids, F, R, m->n_adapters, w.meta, w.frame_of_row, w.adapter_of_row, dev_status, st));
 
     // tokens: x[f][0] = cls + pos[0]; x[f][1 + t] = patch_t W_pe + b_pe + pos[1 + t]
-    POLY_TRY(launch_im2col(frames, w.patches, F, m->H, m->W, m->patch, dt, st));
-    POLY_TRY(launch_cls(w.xa, base->cls, base->pos, F, T, D, st));
+    POLY_TRY(launch_im2col(frames, w.patches, F, m->H, m->W, m->patch, dt, w.xa, base->cls, base->pos, T, D, out_merged,
+                           out_merged ? (size_t)F * K : 0, st));
     {
         GemmArgs g = {};
         g.A = w.patches; g.Wt = base->patch_w; g.bias = base->patch_b;

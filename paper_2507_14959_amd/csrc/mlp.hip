@@ -94,8 +94,8 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
         // gain, shift and biases as well: requested after the weight stream has started they would arrive behind it
         gbv = ln_gb_load<KT>(a.ln_g, a.ln_b, tid);
 #pragma unroll
-        for (int j = 0; j < ML_MAX_DM / 256; ++j) b1v[j] = tid + 256 * j < Dm ? a.b1[tid + 256 * j] : 0.f;
-        if (tid < D) b2v = a.b2[tid];
+        for (int j = 0; j < ML_MAX_DM / 256; ++j) b1v[j] = a.b1[min(tid + 256 * j, Dm - 1)];   // unconditional: see ln_gb_load
+        b2v = a.b2[min(tid, D - 1)];
     }
 
     MLP_TS(1);

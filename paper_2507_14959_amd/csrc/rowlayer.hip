@@ -23,6 +23,13 @@
 
 #include <type_traits>
 
+// phase timestamps for tuning; a test harness defines the macros before including this file
+#ifndef LY_TS
+#define LY_TS(i)
+#define LY_TS_END
+#define LY_TS_BYTES 0
+#endif
+
 namespace {
 
 constexpr int LY_NS = 5;            // LDS stages of the weight stream
@@ -44,13 +51,14 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
     bf16_t *As = lds, *Ws = lds + A_EL;
     float *b1_s = (float *)(lds + A_EL + LY_NS * IT_EL);   // [Dm]
-    float *bias_s = b1_s + LY_MAX_DM;                      // [D] bp in phase A, [3 D] bq in phase C
-    float *b2_s = bias_s + LY_MAX_NQ;                      // [D]
+    float *bq_s = b1_s + LY_MAX_DM;                        // [3 D]
+    float *bp_s = bq_s + LY_MAX_NQ;                        // [D]
+    float *b2_s = bp_s + D;                                // [D]
     float *gb2_s = b2_s + D;                               // LayerNorm2 gain [D], shift [D]
     float *gbq_s = gb2_s + 2 * D;                          // LayerNorm1' gain, shift
-    float *dump_s = gbq_s + 2 * D;                         // 64 words nobody reads (L2 warm-up loads)
-    bf16_t *at_s = (bf16_t *)(dump_s + 64);                // At_k of the current phase: [16][LY_AT_STRIDE]
+    bf16_t *at_s = (bf16_t *)(gbq_s + 2 * D);              // At_k of the current phase: [16][LY_AT_STRIDE]
 
+    LY_TS(0);
     const int tiles = (a.T + 63) / 64;
     const int ob = blockIdx.x / tiles, t0 = (blockIdx.x % tiles) * 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -123,21 +131,22 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             const bf16_t *src = a.o + ((size_t)ob * a.T + min(t0 + (tid >> 2), a.T - 1)) * D + 8 * (tid & 3);
 #pragma unroll
             for (int i = 0; i < D / 32; ++i) pv[i] = *(const bf16x8 *)(src + 32 * i);
-            if (tid < D) bpv = a.bp[tid];
+            bpv = a.bp[min(tid, D - 1)];
         }
         gb2v = ln_gb_load<KT>(a.ln2_g, a.ln2_b, tid);
 #pragma unroll
-        for (int j = 0; j < LY_MAX_DM / 256; ++j) b1v[j] = tid + 256 * j < Dm ? a.b1[tid + 256 * j] : 0.f;
-        if (tid < D) b2v = a.b2[tid];
+        for (int j = 0; j < LY_MAX_DM / 256; ++j) b1v[j] = a.b1[min(tid + 256 * j, Dm - 1)];   // unconditional: see ln_gb_load
+        b2v = a.b2[min(tid, D - 1)];
         if (HAS_QKV) {
             gbqv = ln_gb_load<KT>(a.lnq_g, a.lnq_b, tid);
 #pragma unroll
-            for (int j = 0; j < (LY_MAX_NQ + 255) / 256; ++j) bqv[j] = tid + 256 * j < Nq ? a.bq[tid + 256 * j] : 0.f;
+            for (int j = 0; j < (LY_MAX_NQ + 255) / 256; ++j) bqv[j] = a.bq[min(tid + 256 * j, Nq - 1)];
         }
     } else if (res_early) {
         load_res(ob);
     }
 
+    LY_TS(1);
     const int n_out = a.n_out_dev ? min(*a.n_out_dev, a.n_out) : a.n_out;
     if (ob >= n_out) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -164,12 +173,10 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
 
     if (loader) {
         if (!res_early) load_res(a.res_block_of_out[ob]);
-        // only two items for now -- the rows above are still on their way and would be slowed down by more
-        // (At_k first: the wait for the first chunks then covers it -- loads complete in issue order)
+        // the first items only (all of phase A, or two of B) -- the rows above are still on their way and would be slowed
+        // down by more.  At_k first: the wait for the first chunks then covers it (loads complete in issue order).
         if (lora_p) issue_at(a.Apt + (size_t)k_ad * a.r * D, a.r);
-        refill(-1, 1);
-        l2_warm(a.W1t, (long)Dm * D * 2, lds_addr_of(dump_s), lt, 256);
-        l2_warm(a.W2t, (long)Dm * D * 2, lds_addr_of(dump_s), lt, 256);
+        refill(-1, HAS_PROJ ? KT - 1 : 1);
     } else {
         // prologue of the computing waves: what they requested -> LDS
         if (HAS_PROJ) {
@@ -178,16 +185,23 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
                 const int k = 8 * (4 * i + (tid & 3));
                 *(bf16x8 *)(As + (k >> 6) * 4096 + tile_off(tid >> 2, (k & 63) >> 3)) = pv[i];
             }
-            if (tid < D) bias_s[tid] = bpv;
+            if (tid < D) bp_s[tid] = bpv;
         }
         ln_gb_store<KT>(gb2v, gb2_s, tid);
-        if (HAS_QKV) ln_gb_store<KT>(gbqv, gbq_s, tid);
+        if (HAS_QKV) {
+            ln_gb_store<KT>(gbqv, gbq_s, tid);
+#pragma unroll
+            for (int j = 0; j < (LY_MAX_NQ + 255) / 256; ++j)
+                if (tid + 256 * j < Nq) bq_s[tid + 256 * j] = bqv[j];
+        }
 #pragma unroll
         for (int j = 0; j < LY_MAX_DM / 256; ++j)
             if (tid + 256 * j < Dm) b1_s[tid + 256 * j] = b1v[j];
         if (tid < D) b2_s[tid] = b2v;
     }
+    LY_TS(2);
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // B0: o rows, biases, gains are in LDS
+    LY_TS(3);
 
     const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     const bf16x4 zero4 = {0, 0, 0, 0};
@@ -224,7 +238,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     // one or two chunks of a plain linear against the resident rows: acc starts from the bias; operands are fetched one
     // K step (16) ahead of the MFMAs that use them (LDS latency is a hundred-odd cycles, and the compiler on its own
     // keeps only two or three reads in flight)
-    auto linear_step = [&](f32x16 &acc0, f32x16 &acc1, int c0, int pos0, int N, auto PAIR) {
+    auto linear_step = [&](f32x16 &acc0, f32x16 &acc1, int c0, int pos0, int N, const float *bias_s, auto PAIR) {
         constexpr bool pair = decltype(PAIR)::value;
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         const bf16_t *st0 = Ws + (pos0 % LY_NS) * IT_EL, *st1 = Ws + ((pos0 + 1) % LY_NS) * IT_EL;
@@ -267,29 +281,33 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     if (HAS_PROJ) {
         constexpr int SA = (KT + 1) / 2;
         if (loader) {
-            refill(-1, capA);
+            // (the ring is refilled after each step's barrier, never before it: a loader that is still issuing -- it is held
+            // at the issue stage while the L2 path is busy -- would keep every wave waiting at that barrier)
             for (int s = 0; s < SA; ++s) {
                 wait_item(min(2 * s + 1, KT - 1));
                 if (s == 0 && lora_p) issue_bt(a.Bpt + (size_t)k_ad * D * a.r, D, a.r);     // the computing waves hold their fragments by now
                 refill(2 * s - 1, capA);
             }
             rl_wait_barrier<0>();                                               // Bf: Bt_k has landed
+            LY_TS(5);
             asm volatile("s_barrier" ::: "memory");                             // Bs: the tile is complete
+            LY_TS(6);
 #pragma unroll
             for (int i = 0; i < NV; ++i) xr[i] += *(const f32x4 *)(xtile + (lt >> 2) * XSTRIDE + (4 * i + (lt & 3)) * 16);
             ln_finish<KT, 4>(xr, gb2_s, a.eps, As, lt);
+            LY_TS(7);
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bl: LayerNorm2(x') is in As, the tile is dead
-            refill(PB - 1, capB);
         } else {
             load_fa();
             f32x16 accp[KT + 1];
 #pragma unroll
             for (int s = 0; s < SA; ++s) {
-                if (2 * s + 1 < KT) linear_step(accp[2 * s], accp[2 * s + 1], 2 * s, 2 * s, D, std::true_type{});
-                else linear_step(accp[2 * s], accp[2 * s], 2 * s, 2 * s, D, std::false_type{});
+                if (2 * s + 1 < KT) linear_step(accp[2 * s], accp[2 * s + 1], 2 * s, 2 * s, D, bp_s, std::true_type{});
+                else linear_step(accp[2 * s], accp[2 * s], 2 * s, 2 * s, D, bp_s, std::false_type{});
             }
             bf16x8 fs = zero8;
             if (lora_p) fs = shrink(a.r);                                       // At_k landed before the first chunk did
+            LY_TS(4);
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bf
             if (lora_p) {
 #pragma unroll
@@ -302,14 +320,16 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
 #pragma unroll
                 for (int g = 0; g < 4; ++g)
                     *(f32x4 *)(trow + (c * 64 + 8 * g) * 4) = f32x4{accp[c][4 * g], accp[c][4 * g + 1], accp[c][4 * g + 2], accp[c][4 * g + 3]};
+            LY_TS(5);
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bs
+            LY_TS(6);
             asm volatile("s_barrier" ::: "memory");                             // Bl
+            LY_TS(7);
         }
     } else {
         if (loader) {
             ln_finish<KT, 4>(xr, gb2_s, a.eps, As, lt);
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bl: LayerNorm2(x') is in As
-            refill(PB - 1, capB);
         } else {
             asm volatile("s_barrier" ::: "memory");                             // Bl
         }
@@ -323,6 +343,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             wait_item(NA + need_at(h));
             refill(h >= 1 ? PB + need_at(h - 1) : PB - 1, capB);
         }
+        LY_TS(8);
         rl_wait_barrier<0>();                                                   // Be: every item of B is consumed
         if (lora_q) issue_at(a.Aqt + (size_t)k_ad * a.r * D, a.r);              // before the chunks of C, whose wait then covers it
         refill(HAS_QKV ? PC - 1 : 0, HAS_QKV ? PC + 1 : -1);                    // (the tile still needs stages 0-2)
@@ -330,17 +351,22 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         float *dst = a.x_out + ((size_t)ob * a.T + t0 + (lt >> 2)) * D + 4 * (lt & 3);
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
-            xr[i] += *(const f32x4 *)(xtile + (lt >> 2) * XSTRIDE + (4 * i + (lt & 3)) * 16) + *(const f32x4 *)(b2_s + 4 * (4 * i + (lt & 3)));
+            xr[i] += *(const f32x4 *)(xtile + (lt >> 2) * XSTRIDE + (4 * i + (lt & 3)) * 16);
             if ((lt >> 2) < rows) *(f32x4 *)(dst + 16 * i) = xr[i];
         }
         if (HAS_QKV) ln_finish<KT, 4>(xr, gbq_s, a.eps, As, lt);
+        LY_TS(9);
     } else {
         load_fa();
         f32x16 hcur, hnext;                      // first product of chunks h - 1 / h: row lm, columns wc*32 + 8*(e/4) + 4*lh + e%4
 #pragma unroll
         for (int p = 0; p < KT; ++p)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) y[p][e] = 0.f;
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const f32x4 b = *(const f32x4 *)(b2_s + wc * 32 * KT + p * 32 + 8 * g4 + 4 * lh);   // the accumulators start from b2
+#pragma unroll
+                for (int z = 0; z < 4; ++z) y[p][4 * g4 + z] = b[z];
+            }
 #pragma unroll
         for (int e = 0; e < 16; ++e) hcur[e] = hnext[e] = 0.f;
         bf16_t *Hs = As;                         // hidden tiles [64 rows][64 columns of a chunk], chunk c in tile c & 1 (As is dead
@@ -417,6 +443,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         for (int h = 2; h < nch; ++h) compute_step(T_{}, T_{}, T_{}, h);
         compute_step(F_{}, T_{}, T_{}, nch);
         compute_step(F_{}, F_{}, T_{}, nch + 1);
+        LY_TS(8);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // Be: the ring positions of B are consumed
         char *trow = xtile + (wr * 32 + lm) * XSTRIDE + (wc * 32 * KT + 4 * lh) * 4;
 #pragma unroll
@@ -424,21 +451,17 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4)
                 *(f32x4 *)(trow + (p * 32 + 8 * g4) * 4) = f32x4{y[p][4 * g4], y[p][4 * g4 + 1], y[p][4 * g4 + 2], y[p][4 * g4 + 3]};
+        LY_TS(9);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // By
-        if (HAS_QKV) {
-#pragma unroll
-            for (int j = 0; j < (LY_MAX_NQ + 255) / 256; ++j)
-                if (tid + 256 * j < Nq) bias_s[tid + 256 * j] = bqv[j];
-        }
     }
     if (!HAS_QKV) return;
 
     // ================================================================ phase C: qkv = LayerNorm1'(x'') Wq + bq + lora
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");             // Bz: LayerNorm1'(x'') is in As, bq in LDS, the tile is dead
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");             // Bz: LayerNorm1'(x'') is in As, the tile is dead
+    LY_TS(10);
     f32x16 acc[LY_MAXCH + 1];                    // acc[c][e]: row wr*32 + lm, column c*64 + wc*32 + 8*(e/4) + 4*lh + e%4
     const int i0q = NA + NQ;                     // first item of C
     if (loader) {
-        refill(PC - 1, 1 << 30);
         for (int s = 0; 2 * s < nchq; ++s) {
             wait_item(i0q + min(2 * s + 1, nchq - 1));
             if (s == 0 && lora_q) issue_bt(a.Bqt + (size_t)k_ad * Nq * a.r, Nq, a.r);   // the computing waves hold their fragments by now
@@ -451,11 +474,12 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
 #pragma unroll
         for (int s = 0; s < (LY_MAXCH + 1) / 2; ++s) {
             // uniform conditions, written as guards (not a break) so that the loop unrolls and acc stays in registers
-            if (2 * s + 1 < nchq) linear_step(acc[2 * s], acc[2 * s + 1], 2 * s, PC + 2 * s, Nq, std::true_type{});
-            else if (2 * s < nchq) linear_step(acc[2 * s], acc[2 * s], 2 * s, PC + 2 * s, Nq, std::false_type{});
+            if (2 * s + 1 < nchq) linear_step(acc[2 * s], acc[2 * s + 1], 2 * s, PC + 2 * s, Nq, bq_s, std::true_type{});
+            else if (2 * s < nchq) linear_step(acc[2 * s], acc[2 * s], 2 * s, PC + 2 * s, Nq, bq_s, std::false_type{});
         }
         bf16x8 fs = zero8;
         if (lora_q) fs = shrink(a.r);                                           // At_k landed before the first chunk did
+        LY_TS(11);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // Bf2
         if (lora_q) {
 #pragma unroll
@@ -478,7 +502,9 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             }
         }
     }
+    LY_TS(12);
     __syncthreads();
+    LY_TS(13);
     {
         const int qstride = ((Nq * 2 + 255) & ~255) + 16, pieces = (Nq * 2) >> 4;
         char *out = (char *)a.qkv_out + ((size_t)ob * a.T + t0) * Nq * 2;
@@ -487,12 +513,14 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             *(f32x4 *)(out + (size_t)row * Nq * 2 + p * 16) = *(const f32x4 *)((const char *)lds + row * qstride + p * 16);
         }
     }
+    LY_TS(14);
+    LY_TS_END;
 }
 
 template <int KT, bool HAS_PROJ, bool HAS_QKV> int launch_layer_t(const RowLayerArgs &a, hipStream_t st)
 {
     constexpr int D = 64 * KT;
-    constexpr int LDS = ((KT < 2 ? 2 : KT) + LY_NS * KT) * 64 * 64 * 2 + (LY_MAX_DM + LY_MAX_NQ + D + 4 * D + 64) * 4 + 16 * LY_AT_STRIDE * 2;
+    constexpr int LDS = ((KT < 2 ? 2 : KT) + LY_NS * KT) * 64 * 64 * 2 + (LY_MAX_DM + LY_MAX_NQ + 2 * D + 4 * D) * 4 + 16 * LY_AT_STRIDE * 2 + LY_TS_BYTES;
     static_assert(LDS <= 160 * 1024, "LDS budget");
     auto kern = rowlayer_kernel<KT, HAS_PROJ, HAS_QKV>;
     if (LDS > 64 * 1024) {

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
         // gain, shift and bias as well: requested after the W stream has started they would arrive behind it
         if (a.x_ln) gbv = ln_gb_load<KT>(a.ln_g, a.ln_b, tid);
 #pragma unroll
-        for (int j = 0; j < (RL_MAXCH * RL_BNC + 255) / 256; ++j) bv[j] = a.bias && tid + 256 * j < a.N ? a.bias[tid + 256 * j] : 0.f;
+        for (int j = 0; j < (RL_MAXCH * RL_BNC + 255) / 256; ++j) bv[j] = a.bias ? a.bias[min(tid + 256 * j, a.N - 1)] : 0.f;   // no per-lane condition: see ln_gb_load
     }
 
     RL_TS(1);

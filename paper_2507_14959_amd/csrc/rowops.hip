@@ -40,29 +40,31 @@ __global__ void prep_kernel(const int32_t *row_offsets, const int32_t *adapter_i
 // ------------------------------------------------------------------ patch gathering
 // patches[(f*P + ty*gw + tx)][(i*p + j)*3 + c] = frame[f][ty*p + i][tx*p + j][c]; a run of 3p values
 // (fixed i) is contiguous in the NHWC frame.
-template <typename T>
-__global__ void im2col_kernel(const T *frames, T *patches, int F, int H, int W, int p)
+// VEC elements (16 bytes) per thread when the run length allows it.  The same launch also writes the class-token
+// rows x[f][0][:] = cls + pos[0] and clears the merged-score buffer (both are needed much later: two launches less).
+template <typename T, int VEC>
+__global__ void im2col_kernel(const T *frames, T *patches, int F, int H, int W, int p, float *x, const float *cls, const float *pos,
+                              int T_tok, int D, float *merged, size_t n_merged)
 {
-    const int gw = W / p, gh = H / p, run = 3 * p;
+    const int gw = W / p, gh = H / p, run = 3 * p / VEC;         // vectors per contiguous run
     const size_t total = (size_t)F * gh * gw * p * run;
-    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+    const size_t gtid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, gsz = (size_t)gridDim.x * blockDim.x;
+    typedef T vec_t __attribute__((ext_vector_type(VEC)));
+    for (size_t idx = gtid; idx < total; idx += gsz) {
         size_t q = idx;
         const int e = q % run; q /= run;
         const int i = q % p; q /= p;
         const int tx = q % gw; q /= gw;
         const int ty = q % gh; const size_t f = q / gh;
-        patches[idx] = frames[((f * H + (size_t)ty * p + i) * W + (size_t)tx * p) * 3 + e];
+        const T *src = frames + ((f * H + (size_t)ty * p + i) * W + (size_t)tx * p) * 3 + (size_t)e * VEC;
+        if (VEC == 1) patches[idx] = *src;
+        else *(vec_t *)(patches + idx * VEC) = *(const vec_t *)src;
     }
-}
-
-// x[f][0][:] = cls + pos[0]
-__global__ void cls_kernel(float *x, const float *cls, const float *pos, int F, int T, int D)
-{
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx < F * D) {
-        const int f = idx / D, c = idx % D;
-        x[(size_t)f * T * D + c] = cls[c] + pos[c];
+    for (size_t idx = gtid; idx < (size_t)F * D; idx += gsz) {
+        const size_t f = idx / D; const int c = idx % D;
+        x[f * T_tok * D + c] = cls[c] + pos[c];
     }
+    for (size_t idx = gtid; idx < n_merged; idx += gsz) merged[idx] = 0.f;
 }
 
 // ------------------------------------------------------------------ LayerNorm
@@ -184,11 +186,6 @@ __global__ __launch_bounds__(64) void head_kernel(const float *x, const int *src
 }
 
 // ------------------------------------------------------------------ merge to label space
-__global__ void zero_kernel(float *p, size_t n)
-{
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0.f;
-}
-
 // scores are in (0, 1): the order of positive floats is the order of their bit patterns, so an integer
 // atomic max merges overlapping adapters without depending on arrival order
 __global__ void merge_kernel(const float *scores, const int *frame_of_row, const int *adapter_of_row, const int32_t *class_map,
@@ -216,22 +213,23 @@ int launch_prep(const int32_t *row_offsets, const int32_t *adapter_ids, int F, i
     return hip_ok();
 }
 
-int launch_im2col(const void *frames, void *patches, int F, int H, int W, int p, int dtype, hipStream_t st)
+int launch_im2col(const void *frames, void *patches, int F, int H, int W, int p, int dtype, float *x, const float *cls, const float *pos,
+                  int T_tok, int D, float *merged, size_t n_merged, hipStream_t st)
 {
     const size_t total = (size_t)F * H * W * 3;
-    if (total == 0) return POLY_OK;
-    const unsigned blocks = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
-    if (dtype == POLY_BF16)
-        POLY_LAUNCH(POLY_STAGE_OTHER, im2col_kernel<bf16_t>, dim3(blocks), dim3(256), st, (const bf16_t *)frames, (bf16_t *)patches, F, H, W, p);
-    else
-        POLY_LAUNCH(POLY_STAGE_OTHER, im2col_kernel<float>, dim3(blocks), dim3(256), st, (const float *)frames, (float *)patches, F, H, W, p);
-    return hip_ok();
-}
-
-int launch_cls(float *x, const float *cls, const float *pos, int F, int T, int D, hipStream_t st)
-{
-    if (F == 0) return POLY_OK;
-    POLY_LAUNCH(POLY_STAGE_OTHER, cls_kernel, dim3((F * D + 255) / 256), dim3(256), st, x, cls, pos, F, T, D);
+    if (total == 0 && n_merged == 0) return POLY_OK;
+    // 16-byte vectors when a run of 3p elements is a whole number of them and rows of the frame keep them aligned
+    const int vec = dtype == POLY_BF16 ? 8 : 4;
+    const bool wide = (3 * p) % vec == 0 && (3 * W) % vec == 0 && ((uintptr_t)frames & 15) == 0 && ((uintptr_t)patches & 15) == 0;
+    const size_t work = (wide ? total / vec : total) > n_merged ? (wide ? total / vec : total) : n_merged;
+    const unsigned blocks = (unsigned)((work + 255) / 256 > 65536 ? 65536 : (work + 255) / 256 < 1 ? 1 : (work + 255) / 256);
+    if (dtype == POLY_BF16) {
+        if (wide) POLY_LAUNCH(POLY_STAGE_OTHER, (im2col_kernel<bf16_t, 8>), dim3(blocks), dim3(256), st, (const bf16_t *)frames, (bf16_t *)patches, F, H, W, p, x, cls, pos, T_tok, D, merged, n_merged);
+        else POLY_LAUNCH(POLY_STAGE_OTHER, (im2col_kernel<bf16_t, 1>), dim3(blocks), dim3(256), st, (const bf16_t *)frames, (bf16_t *)patches, F, H, W, p, x, cls, pos, T_tok, D, merged, n_merged);
+    } else {
+        if (wide) POLY_LAUNCH(POLY_STAGE_OTHER, (im2col_kernel<float, 4>), dim3(blocks), dim3(256), st, (const float *)frames, (float *)patches, F, H, W, p, x, cls, pos, T_tok, D, merged, n_merged);
+        else POLY_LAUNCH(POLY_STAGE_OTHER, (im2col_kernel<float, 1>), dim3(blocks), dim3(256), st, (const float *)frames, (float *)patches, F, H, W, p, x, cls, pos, T_tok, D, merged, n_merged);
+    }
     return hip_ok();
 }
 
@@ -286,7 +284,6 @@ int launch_merge(const float *scores, const int *frame_of_row, const int *adapte
 {
     const size_t n = (size_t)F * K;
     if (n == 0) return POLY_OK;
-    POLY_LAUNCH(POLY_STAGE_OTHER, zero_kernel, dim3((unsigned)((n + 255) / 256 > 4096 ? 4096 : (n + 255) / 256)), dim3(256), st, merged, n);
     if (R_cap > 0)
         POLY_LAUNCH(POLY_STAGE_OTHER, merge_kernel, dim3((R_cap * C + 255) / 256), dim3(256), st, scores, frame_of_row, adapter_of_row, class_map,
                            C, K, meta, merged);

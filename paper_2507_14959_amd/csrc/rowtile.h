@@ -69,12 +69,15 @@ __device__ __forceinline__ void ln_load(const float *xblock, int T, int t0, int 
 #pragma unroll
     for (int i = 0; i < NV; ++i) v[i] = *(const f32x4 *)(xr + 4 * TPR * i);
 }
-// gain and shift: requested by threads 0 .. K/2 - 1 (ln_gb_load, early), written to LDS later (ln_gb_store)
+// gain and shift: requested early (ln_gb_load), written to LDS later by threads 0 .. K/2 - 1 (ln_gb_store)
 template <int KT> __device__ __forceinline__ f32x4 ln_gb_load(const float *ln_g, const float *ln_b, int tid)
 {
+    // every thread loads (a load under a per-lane condition makes the compiler wait for it on the spot); the
+    // threads past K/2 repeat the last piece and drop it in ln_gb_store
     constexpr int K = 64 * KT;
-    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    return tid < K / 2 ? (tid < K / 4 ? *(const f32x4 *)(ln_g + 4 * tid) : *(const f32x4 *)(ln_b + 4 * (tid - K / 4))) : zero;
+    const int i = min(tid, K / 2 - 1);
+    const float *src = i < K / 4 ? ln_g + 4 * i : ln_b + 4 * (i - K / 4);
+    return *(const f32x4 *)src;
 }
 template <int KT> __device__ __forceinline__ void ln_gb_store(f32x4 v, float *gb_s, int tid)
 {
@@ -98,14 +101,14 @@ __device__ __forceinline__ void ln_finish(const f32x4 (&v)[64 * KT / TPR / 4], c
         for (int z = 0; z < 4; ++z) { const float d = v[i][z] - mean; q = fmaf(d, d, q); }
 #pragma unroll
     for (int m = 1; m < TPR; m <<= 1) q += __shfl_xor(q, m, 64);
-    const float inv = rsqrtf(q * (1.0f / K) + eps);
+    const float inv = rsqrtf(q * (1.0f / K) + eps), nmi = -mean * inv;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int k = 4 * (TPR * i + part);          // first of this piece's 4 elements
         const f32x4 g = *(const f32x4 *)(gb_s + k), b = *(const f32x4 *)(gb_s + K + k);
         bf16x4 o;
 #pragma unroll
-        for (int z = 0; z < 4; ++z) o[z] = (bf16_t)((v[i][z] - mean) * inv * g[z] + b[z]);
+        for (int z = 0; z < 4; ++z) o[z] = (bf16_t)fmaf(fmaf(v[i][z], inv, nmi), g[z], b[z]);   // ((x - mean) inv) g + b
         // tile k / 64, 16-byte chunk (k % 64) / 8, first or second half of it
         *(bf16x4 *)(As + (k >> 6) * (64 * 64) + tile_off(row, (k & 63) >> 3) + (k & 4)) = o;
     }

@@ -82,6 +82,36 @@ __device__ __forceinline__ f32x4 gelu_poly4(f32x4 x)
     return q;
 }
 
+// erf-GELU through a table of Phi in LDS, for kernels whose inner loop is bound by the number of instructions it
+// issues: GELU(x) = x * Phi(x), Phi linearly interpolated between samples 1/64 apart on [-4.5, 4.5] (clamped
+// outside: Phi(-4.5) = 3.4e-6, 1 - Phi(4.5) = 3.4e-6).  Interpolation error <= h^2 / 8 * max|Phi''| = 7.4e-6.
+// Entry i holds (Phi(x_i), Phi(x_{i+1}) - Phi(x_i)), x_i = (i - 288) / 64, i = 0 .. 576: 4616 bytes.
+constexpr int GELU_TAB_ENTRIES = 577;
+__device__ __forceinline__ void gelu_tab_build(float *tab, int tid, int nthreads)
+{
+    for (int i = tid; i < GELU_TAB_ENTRIES; i += nthreads) {
+        const float x0 = (i - 288) * (1.0f / 64), x1 = x0 + 1.0f / 64;
+        const float p0 = 0.5f * erfcf(-x0 * 0.70710678118654752440f), p1 = i < GELU_TAB_ENTRIES - 1 ? 0.5f * erfcf(-x1 * 0.70710678118654752440f) : p0;
+        tab[2 * i] = p0;
+        tab[2 * i + 1] = p1 - p0;
+    }
+}
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ f32x4 gelu_tab4(f32x4 x, const float *tab)
+{
+    f32x4 fr;
+    f32x2 e[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float t = fmaf(__builtin_amdgcn_fmed3f(x[i], -4.5f, 4.5f), 64.0f, 288.0f), fl = floorf(t);
+        fr[i] = t - fl;
+        e[i] = *(const f32x2 *)(tab + 2 * (int)fl);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fr[i] = x[i] * fmaf(fr[i], e[i][1], e[i][0]);
+    return fr;
+}
+
 // ---- launch with optional per-stage timing (profile.hip) ----
 bool poly_prof_next(int stage, hipEvent_t *a, hipEvent_t *b);
 

@@ -57,6 +57,9 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     float *gb2_s = b2_s + D;                               // LayerNorm2 gain [D], shift [D]
     float *gbq_s = gb2_s + 2 * D;                          // LayerNorm1' gain, shift
     bf16_t *at_s = (bf16_t *)(gbq_s + 2 * D);              // At_k of the current phase: [16][LY_AT_STRIDE]
+    // Phi table of the GELU (phase B): behind the two hidden tiles in the activation-row area when that has 24 KB, else in
+    // a region of its own (narrower models leave LDS to spare)
+    float *gelu_s = KT == 3 ? (float *)(As + 2 * 4096) : (float *)(at_s + 16 * LY_AT_STRIDE);
 
     LY_TS(0);
     const int tiles = (a.T + 63) / 64;
@@ -341,6 +344,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         auto need_at = [&](int h) { return h < 2 ? h : min(2 * h - 1, NQ - 1); };
         for (int h = 0; h < nch + 2; ++h) {
             wait_item(NA + need_at(h));
+            if (h == 0) gelu_tab_build(gelu_s, lt, 256);   // every computing wave holds its fragments of LayerNorm2(x') by now; first used in step 1
             refill(h >= 1 ? PB + need_at(h - 1) : PB - 1, capB);
         }
         LY_TS(8);
@@ -415,7 +419,9 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
                     for (int kt = 0; kt < KT; ++kt) hnext = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[kk & 1][kt], fa[kt * 4 + kk], hnext, 0, 0, 0);
                 }
                 if (dg) {
-                    const f32x4 v = gelu_poly4(f32x4{hcur[4 * kk], hcur[4 * kk + 1], hcur[4 * kk + 2], hcur[4 * kk + 3]} + b[kk]);
+                    // a quarter of the chunk's GELU per K step, through the Phi table (fewer instructions than the polynomial:
+                    // this loop is bound by the number of instructions the wave issues)
+                    const f32x4 v = gelu_tab4(f32x4{hcur[4 * kk], hcur[4 * kk + 1], hcur[4 * kk + 2], hcur[4 * kk + 3]} + b[kk], gelu_s);
                     const bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
                     *(bf16x4 *)(Hw + tile_off(wr * 32 + lm, 4 * wc + kk) + 4 * lh) = o;
                 }
@@ -425,7 +431,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
 #pragma unroll
                     for (int i = 0; i < NM; ++i) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, (64 + NM - 1) / NM, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, (40 + NM - 1) / NM, 0);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -520,7 +526,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
 template <int KT, bool HAS_PROJ, bool HAS_QKV> int launch_layer_t(const RowLayerArgs &a, hipStream_t st)
 {
     constexpr int D = 64 * KT;
-    constexpr int LDS = ((KT < 2 ? 2 : KT) + LY_NS * KT) * 64 * 64 * 2 + (LY_MAX_DM + LY_MAX_NQ + 2 * D + 4 * D) * 4 + 16 * LY_AT_STRIDE * 2 + LY_TS_BYTES;
+    constexpr int LDS = ((KT < 2 ? 2 : KT) + LY_NS * KT) * 64 * 64 * 2 + (LY_MAX_DM + LY_MAX_NQ + 2 * D + 4 * D) * 4 + 16 * LY_AT_STRIDE * 2 + (KT == 3 ? 0 : GELU_TAB_ENTRIES * 8) + LY_TS_BYTES;
     static_assert(LDS <= 160 * 1024, "LDS budget");
     auto kern = rowlayer_kernel<KT, HAS_PROJ, HAS_QKV>;
     if (LDS > 64 * 1024) {

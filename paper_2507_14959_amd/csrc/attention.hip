@@ -14,55 +14,91 @@ constexpr float LOG2E = 1.4426950408889634f;
 
 template <int NKT>  // 32-key tiles: T <= 32 * NKT
 __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_t *out, int T, int D, int heads, int n_blocks,
-                                                        const int *n_blocks_dev)
+                                                        const int *n_blocks_dev, int nsplit)
 {
     constexpr int TKP = NKT * 32;
     constexpr int KS = 64 + 8;    // Ks row stride (elements): 144 B, 16-byte aligned
     constexpr int VS = TKP + 8;   // Vt row stride: multiple of 8 elements
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[TKP * KS];
-    __shared__ __attribute__((aligned(16))) bf16_t Vt[64 * VS];
+    constexpr int OS = 64 + 8;    // row stride of a wave's output tile
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    bf16_t *Ks = smem;                       // [TKP][KS]
+    bf16_t *Vt = Ks + TKP * KS;              // [64][VS]
+    bf16_t *Ot = Vt + 64 * VS;               // [waves][32][OS]: finished outputs of a wave's query tile, for row-wise stores
 
+    // nsplit workgroups share one (block, head): each stages all keys and values and takes every nsplit-th round of
+    // query tiles, so that no wave needs a second round at T = 197
     const int nb = n_blocks_dev ? min(*n_blocks_dev, n_blocks) : n_blocks;
-    const int b = blockIdx.x / heads, hd = blockIdx.x % heads;
+    const int part = blockIdx.x % nsplit, bh = blockIdx.x / nsplit;
+    const int b = bh / heads, hd = bh % heads;
     if (b >= nb) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lm = lane & 31, lh = lane >> 5;
     const size_t ld = (size_t)3 * D;
     const bf16_t *base = qkv + (size_t)b * T * ld + hd * 64;
     const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-
     const int nthreads = blockDim.x, nwaves = nthreads >> 6;
-    for (int v = tid; v < TKP * 8; v += nthreads) {
-        const int key = v >> 3, c8 = (v & 7) * 8;
-        bf16x8 kk = zero8, vv = zero8;
-        if (key < T) {
-            kk = *(const bf16x8 *)(base + (size_t)key * ld + D + c8);
-            vv = *(const bf16x8 *)(base + (size_t)key * ld + 2 * D + c8);
-        }
-        *(bf16x8 *)(Ks + key * KS + c8) = kk;
+    const int nq = (T + 31) / 32;
+
+    // everything this thread will read from global memory is requested up front: its queries (at most two rounds),
+    // then its share of K (16-byte pieces) and of V (an 8 keys x 8 columns block, transposed in registers below)
+    bf16x8 qf[2][4];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) Vt[(c8 + q) * VS + key] = vv[q];
+    for (int rd = 0; rd < 2; ++rd) {
+        const int query = (part * nwaves + wave + rd * nwaves * nsplit) * 32 + lm;
+#pragma unroll
+        for (int ds = 0; ds < 4; ++ds) qf[rd][ds] = query < T ? *(const bf16x8 *)(base + (size_t)query * ld + ds * 16 + lh * 8) : zero8;
+    }
+    constexpr int NKP = NKT <= 4 ? 4 : NKT;        // K pieces (256 NKT) per thread: the workgroup has 64 min(NKT, 4) threads
+    bf16x8 kp[NKP];
+#pragma unroll
+    for (int i = 0; i < NKP; ++i) {
+        const int v = tid + i * nthreads, key = v >> 3;
+        kp[i] = (v < TKP * 8 && key < T) ? *(const bf16x8 *)(base + (size_t)key * ld + D + (v & 7) * 8) : zero8;
+    }
+    for (int blk = tid; blk < (TKP / 8) * 8; blk += nthreads) {
+        const int cb = blk & 7, kb = blk >> 3;       // consecutive lanes: consecutive 16-byte pieces of a row of V
+        bf16x8 vv[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int key = kb * 8 + k;
+            vv[k] = key < T ? *(const bf16x8 *)(base + (size_t)key * ld + 2 * D + cb * 8) : zero8;
+        }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const bf16x8 t = {vv[0][c], vv[1][c], vv[2][c], vv[3][c], vv[4][c], vv[5][c], vv[6][c], vv[7][c]};
+            *(bf16x8 *)(Vt + (cb * 8 + c) * VS + kb * 8) = t;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NKP; ++i) {
+        const int v = tid + i * nthreads;
+        if (v < TKP * 8) *(bf16x8 *)(Ks + (v >> 3) * KS + (v & 7) * 8) = kp[i];
     }
     __syncthreads();
 
-    const int nq = (T + 31) / 32;
-    for (int qs = wave; qs < nq; qs += nwaves) {
-        const int query = qs * 32 + lm;
-        bf16x8 qf[4];
 #pragma unroll
-        for (int ds = 0; ds < 4; ++ds)
-            qf[ds] = query < T ? *(const bf16x8 *)(base + (size_t)query * ld + ds * 16 + lh * 8) : zero8;
+    for (int rd = 0; rd < 2; ++rd) {
+        const int qs = part * nwaves + wave + rd * nwaves * nsplit;
+        if (qs >= nq) break;
+        const int query = qs * 32 + lm;
 
-        // S^T tile kt: rows = keys kt*32 + 8*(e/4) + 4*lh + e%4, column = this lane's query
+        // S^T tile kt: rows = keys kt*32 + 8*(e/4) + 4*lh + e%4, column = this lane's query.  The K fragments of tile
+        // kt + 1 are read while the MFMAs of tile kt run (the scheduling barriers pin that order)
         f32x16 s[NKT];
+        bf16x8 kf[2][4];
+#pragma unroll
+        for (int ds = 0; ds < 4; ++ds) kf[0][ds] = *(const bf16x8 *)(Ks + lm * KS + ds * 16 + lh * 8);
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt) {
+            if (kt + 1 < NKT) {
+#pragma unroll
+                for (int ds = 0; ds < 4; ++ds) kf[(kt + 1) & 1][ds] = *(const bf16x8 *)(Ks + ((kt + 1) * 32 + lm) * KS + ds * 16 + lh * 8);
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int e = 0; e < 16; ++e) s[kt][e] = 0.f;
 #pragma unroll
-            for (int ds = 0; ds < 4; ++ds) {
-                const bf16x8 kf = *(const bf16x8 *)(Ks + (kt * 32 + lm) * KS + ds * 16 + lh * 8);
-                s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ds], s[kt], 0, 0, 0);
-            }
+            for (int ds = 0; ds < 4; ++ds) s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kt & 1][ds], qf[rd][ds], s[kt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
 
         // only the last key tile can hold keys past T (T > 32 * (NKT - 1) by construction)
@@ -95,40 +131,58 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_
                 }
         sum += __shfl_xor(sum, 32, 64);
 
-        // O^T = V^T P^T: rows = head columns, column = this lane's query
+        // O^T = V^T P^T: rows = head columns, column = this lane's query; V^T fragments one step ahead as above
         f32x16 o[2];
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
+        bf16x4 vlo[2][2], vhi[2][2];
+        auto loadv = [&](int st, int sl) {
+            // slots 0..3 = keys kbase + 4*lh + 0..3, slots 4..7 = keys kbase + 8 + 4*lh + 0..3
+            const int kbase = st * 16 + 4 * lh;
 #pragma unroll
-        for (int kt = 0; kt < NKT; ++kt)
-#pragma unroll
-            for (int hs = 0; hs < 2; ++hs) {
-                // slots 0..3 = keys kbase + 4*lh + 0..3, slots 4..7 = keys kbase + 8 + 4*lh + 0..3
-                const int kbase = kt * 32 + hs * 16 + 4 * lh;
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt) {
-                    const bf16_t *vr = Vt + (dt * 32 + lm) * VS + kbase;
-                    const bf16x4 lo = *(const bf16x4 *)vr, hi = *(const bf16x4 *)(vr + 8);
-                    const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kt][hs], o[dt], 0, 0, 0);
-                }
+            for (int dt = 0; dt < 2; ++dt) {
+                const bf16_t *vr = Vt + (dt * 32 + lm) * VS + kbase;
+                vlo[sl][dt] = *(const bf16x4 *)vr;
+                vhi[sl][dt] = *(const bf16x4 *)(vr + 8);
             }
-
-        if (query < T) {
-            const float inv = 1.0f / sum;
-            bf16_t *orow = out + ((size_t)b * T + query) * D + hd * 64;
+        };
+        loadv(0, 0);
 #pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
+        for (int st = 0; st < 2 * NKT; ++st) {
+            if (st + 1 < 2 * NKT) loadv(st + 1, (st + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4 w;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) w[q] = (bf16_t)(o[dt][g * 4 + q] * inv);
-                    *(bf16x4 *)(orow + dt * 32 + 8 * g + 4 * lh) = w;
-                }
+            for (int dt = 0; dt < 2; ++dt) {
+                const bf16x4 lo = vlo[st & 1][dt], hi = vhi[st & 1][dt];
+                const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[st >> 1][st & 1], o[dt], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
+
+        // a lane owns one query: stored from registers, every instruction would touch 32 cache lines with 8 bytes each.
+        // The wave lays its 32 x 64 tile out in LDS and stores 16-byte pieces, 8 lanes per row
+        const float inv = 1.0f / sum;
+        bf16_t *ot = Ot + wave * 32 * OS;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 w;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) w[q] = (bf16_t)(o[dt][g * 4 + q] * inv);
+                *(bf16x4 *)(ot + lm * OS + dt * 32 + 8 * g + 4 * lh) = w;
+            }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // the tile is private to the wave: no barrier
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = i * 8 + (lane >> 3), qrow = qs * 32 + row;
+            const bf16x8 v = *(const bf16x8 *)(ot + row * OS + (lane & 7) * 8);
+            if (qrow < T) *(bf16x8 *)(out + ((size_t)b * T + qrow) * D + hd * 64 + (lane & 7) * 8) = v;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // reads done before the next round overwrites the tile
     }
 }
 
@@ -184,12 +238,26 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *qkv, float *
 }
 
 template <int NKT>
-void launch_bf16(const void *qkv, void *out, int T, int D, int heads, int n_blocks, const int *n_blocks_dev, hipStream_t st)
+int launch_bf16(const void *qkv, void *out, int T, int D, int heads, int n_blocks, const int *n_blocks_dev, hipStream_t st)
 {
     // up to 4 waves, one 32-query tile per wave and round (the score tile of a wave needs most of a SIMD's registers)
-    const int waves = (T + 31) / 32 < 4 ? (T + 31) / 32 : 4;
-    POLY_LAUNCH(POLY_STAGE_ATTN, attn_bf16_kernel<NKT>, dim3((unsigned)(n_blocks * heads)), dim3(64 * waves), st, (const bf16_t *)qkv, (bf16_t *)out, T, D,
-                       heads, n_blocks, n_blocks_dev);
+    const int nq = (T + 31) / 32, waves = nq < 4 ? nq : 4;
+    // split (each half stages all keys and values, but no wave needs a second round) while the launch is small enough
+    // to leave CUs idle or single-occupied; large launches keep one workgroup per (block, head)
+    const int nsplit = nq > 4 && (long)n_blocks * heads <= 512 ? 2 : 1;
+    constexpr int TKP = NKT * 32;
+    constexpr int LDS = (TKP * 72 + 64 * (TKP + 8) + 4 * 32 * 72) * 2;
+    auto kern = attn_bf16_kernel<NKT>;
+    if (LDS > 64 * 1024) {
+        static bool attr_set = false;   // raising the dynamic LDS limit is a per-kernel, process-wide setting
+        if (!attr_set) {
+            if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS) != hipSuccess) return POLY_EHIP;
+            attr_set = true;
+        }
+    }
+    POLY_LAUNCH_SHMEM(POLY_STAGE_ATTN, kern, dim3((unsigned)(n_blocks * heads * nsplit)), dim3(64 * waves), LDS, st, (const bf16_t *)qkv, (bf16_t *)out, T, D,
+                      heads, n_blocks, n_blocks_dev, nsplit);
+    return POLY_OK;
 }
 
 }  // namespace
@@ -201,13 +269,13 @@ int launch_attention(const void *qkv, void *out, int T, int D, int heads, int n_
     if (D != heads * 64) return POLY_EINVAL;
     if (dtype == POLY_BF16) {
         switch ((T + 31) / 32) {
-        case 1: launch_bf16<1>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
-        case 2: launch_bf16<2>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
-        case 3: launch_bf16<3>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
-        case 4: launch_bf16<4>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
-        case 5: launch_bf16<5>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
-        case 6: launch_bf16<6>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
-        case 7: launch_bf16<7>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st); break;
+        case 1: if (launch_bf16<1>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st) != POLY_OK) return POLY_EHIP; break;
+        case 2: if (launch_bf16<2>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st) != POLY_OK) return POLY_EHIP; break;
+        case 3: if (launch_bf16<3>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st) != POLY_OK) return POLY_EHIP; break;
+        case 4: if (launch_bf16<4>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st) != POLY_OK) return POLY_EHIP; break;
+        case 5: if (launch_bf16<5>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st) != POLY_OK) return POLY_EHIP; break;
+        case 6: if (launch_bf16<6>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st) != POLY_OK) return POLY_EHIP; break;
+        case 7: if (launch_bf16<7>(qkv, out, T, D, heads, n_blocks, n_blocks_dev, st) != POLY_OK) return POLY_EHIP; break;
         default: return POLY_EINVAL;  // bf16 attention holds all keys of a block in 64 KB of LDS: T <= 224
         }
     } else {

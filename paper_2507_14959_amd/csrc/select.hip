@@ -28,6 +28,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float *scores, int F,
     __shared__ int size_of[MMAX];
     __shared__ int order[MMAX];                // scan position -> context id
     __shared__ uint64_t cmask[MMAX][KWMAX];    // labels that the context at a scan position provides
+    __shared__ uint64_t mem_id[MMAX][KWMAX], prov_id[MMAX][KWMAX];   // member / provided labels by context id
     __shared__ uint64_t Y[CH][KWMAX];          // Y_t
     __shared__ uint64_t U[CH][KWMAX];          // still uncovered while scanning
     __shared__ uint64_t S[CH];                 // S_t as a mask over scan positions
@@ -40,11 +41,34 @@ __global__ __launch_bounds__(256) void select_kernel(const float *scores, int F,
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int KW = (K + 63) / 64;
 
+    // Membership and provided-label bitsets per (context id, 64-label word), one ballot each.  The loads of eight
+    // words are requested together (a loop that loads, ballots and stores one word at a time pays a full memory
+    // round trip per word), with clamped addresses instead of per-lane conditions.
+    for (int w0 = wave * 8; w0 < M * KW; w0 += 32) {
+        uint8_t mb[8];
+        float ac[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int w = min(w0 + u, M * KW - 1), c = w / KW, l = min((w % KW) * 64 + lane, K - 1);
+            mb[u] = member[(size_t)c * K + l];
+            ac[u] = acc ? acc[(size_t)c * K + l] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int w = w0 + u;
+            if (w < M * KW) {     // uniform
+                const bool in = (w % KW) * 64 + lane < K, mem = in && mb[u] != 0;
+                const uint64_t mm = __ballot(mem), pm = __ballot(mem && (acc == nullptr || ac[u] >= tau));
+                if (lane == 0) { mem_id[w / KW][w % KW] = mm; prov_id[w / KW][w % KW] = pm; }
+            }
+        }
+    }
+    __syncthreads();
     // contexts in scan order: size ascending, id ascending
     if (tid < M) {
-        int s = 0;
-        for (int l = 0; l < K; ++l) s += member[(size_t)tid * K + l] ? 1 : 0;
-        size_of[tid] = s;
+        int sz = 0;
+        for (int j = 0; j < KW; ++j) sz += __popcll(mem_id[tid][j]);
+        size_of[tid] = sz;
     }
     __syncthreads();
     if (tid < M) {
@@ -53,13 +77,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float *scores, int F,
         order[rank] = tid;
     }
     __syncthreads();
-    for (int w = wave; w < M * KW; w += 4) {
-        const int pos = w / KW, j = w % KW, c = order[pos], l = j * 64 + lane;
-        bool p = false;
-        if (l < K) p = member[(size_t)c * K + l] != 0 && (acc == nullptr || acc[(size_t)c * K + l] >= tau);
-        const uint64_t m = __ballot(p);
-        if (lane == 0) cmask[pos][j] = m;
-    }
+    for (int w = tid; w < M * KW; w += 256) cmask[w / KW][w % KW] = prov_id[order[w / KW]][w % KW];
     if (tid == 0) {
         total = 0; total_unc = 0; prevS = 0; prevValid = 0;
         if (state && state->valid) {
@@ -84,12 +102,22 @@ __global__ __launch_bounds__(256) void select_kernel(const float *scores, int F,
     for (int f0 = 0; f0 < F; f0 += CH) {
         const int n = min(CH, F - f0);
         __syncthreads();
-        // Y_t: one ballot per 64 labels
-        for (int w = wave; w < n * KW; w += 4) {
-            const int t = w / KW, j = w % KW, l = j * 64 + lane;
-            const bool a = l < K && scores[(size_t)(f0 + t) * K + l] >= theta;
-            const uint64_t m = __ballot(a);
-            if (lane == 0) { Y[t][j] = m; U[t][j] = m; }
+        // Y_t: one ballot per 64 labels, the scores of eight words requested together (see above)
+        for (int w0 = wave * 8; w0 < n * KW; w0 += 32) {
+            float sv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int w = min(w0 + u, n * KW - 1);
+                sv[u] = scores[(size_t)(f0 + w / KW) * K + min((w % KW) * 64 + lane, K - 1)];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int w = w0 + u;
+                if (w < n * KW) {     // uniform
+                    const uint64_t m = __ballot((w % KW) * 64 + lane < K && sv[u] >= theta);
+                    if (lane == 0) { Y[w / KW][w % KW] = m; U[w / KW][w % KW] = m; }
+                }
+            }
         }
         __syncthreads();
         // greedy cover, one frame per thread

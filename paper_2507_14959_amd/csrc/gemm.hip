@@ -593,12 +593,11 @@ int launch_gemm(const GemmArgs &g, int dtype, hipStream_t st)
         if (g.K % 8 != 0 || (g.S && g.RP % 16 != 0)) return POLY_EINVAL;
         if ((long)g.N * g.K > 0x7fffffffL || (long)g.T * g.K > 0x7fffffffL) return POLY_EINVAL;
         if (g.K % 64 == 0 && g.N % 8 == 0) {
-            static const int variant = getenv("POLY_GEMM_VARIANT") ? atoi(getenv("POLY_GEMM_VARIANT")) : 1;
             // long contractions with many tiles: 256-row tiles (one per 197-token block) cut the L2 -> LDS traffic
             // per flop; short contractions (K = 192) and small batches keep 128-row tiles, whose workgroups are
             // light enough to overlap their load latency and epilogues across a CU
             const long tiles256 = (long)g.n_in * ((g.T + 255) / 256) * ((g.N + 255) / 256);
-            const bool big = variant >= 1 && g.T > 128 && g.K >= 512;
+            const bool big = g.T > 128 && g.K >= 512;
             if (big && g.N % 256 == 0 && tiles256 >= 512) {
                 launch_dma<256, 256, 2, 4, 2>(g, st);
             } else if (big && g.N % 128 == 0 && (long)g.n_in * ((g.N + 127) / 128) >= 512) {

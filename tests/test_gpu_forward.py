@@ -45,6 +45,20 @@ def test_small_models_all_target_sets(dtype, targets, L0, r):
     compare(cfg, w, frames, off, ids, L0, K=cfg.n_adapters * cfg.C)
 
 
+@pytest.mark.parametrize("D,heads,Dm,hw,r,targets,L0", [
+    (64, 1, 128, 48, 4, 3, 0),      # one 64-column tile, T = 37: a single ragged row tile
+    (64, 1, 192, 64, 16, 1, 1),     # T = 65: a full tile and a one-row tile; adapters on qkv only; fan-out at layer 1
+    (128, 2, 256, 64, 12, 3, 0),    # rank 12: the second half of the expand operand is partly empty
+    (192, 3, 768, 40, 8, 3, 2),     # DeiT-tiny widths, T = 26, fan-out at layer 2
+    (192, 3, 320, 72, 16, 2, 0),    # adapters on proj only, Dm = 5 chunks, T = 82
+])
+def test_row_kernels_all_widths(D, heads, Dm, hw, r, targets, L0):
+    """bf16 models whose layers run in the fused row kernels (no adapters on fc1 / fc2): every tile width, ragged tiles."""
+    cfg, w, frames, off, ids = synth.make_small_case(60 + D + r, dtype=synth.DT_BF16, targets=targets, L=4, F=4, r=r, max_set=3,
+                                                      n_adapters=5, D=D, heads=heads, Dm=Dm, hw=hw, patch=8)
+    compare(cfg, w, frames, off, ids, L0, K=cfg.n_adapters * cfg.C)
+
+
 def test_frames_without_adapters_and_empty_batch():
     cfg, w, frames, _, _ = synth.make_small_case(50, dtype=synth.DT_BF16, F=4)
     off, ids = synth.sets_to_csr([[], [1, 0], [], [2]])

@@ -1,6 +1,6 @@
 // Fused softmax attention of one (token block, head) per workgroup; head width 64.
 //
-// bf16: K and V^T of the head are staged once in LDS.  Each wave owns 32 queries at a time and computes
+// bf16: K and V^T of the head are staged once in LDS.  Each wave owns 32 queries (one wave per query tile) and computes
 // S^T = K Q^T on the MFMA (keys down the rows, so every lane holds all scores of ONE query), takes the
 // softmax over its registers in fp32, and feeds the unnormalised probabilities straight back as the B
 // operand of O^T = V^T P^T -- the accumulator layout of S^T is already a valid B layout once the keys of
@@ -13,8 +13,8 @@ namespace {
 constexpr float LOG2E = 1.4426950408889634f;
 
 template <int NKT>  // 32-key tiles: T <= 32 * NKT
-__global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_t *out, int T, int D, int heads, int n_blocks,
-                                                        const int *n_blocks_dev, int nsplit)
+__global__ __launch_bounds__(512) void attn_bf16_kernel(const bf16_t *qkv, bf16_t *out, int T, int D, int heads, int n_blocks,
+                                                        const int *n_blocks_dev)
 {
     constexpr int TKP = NKT * 32;
     constexpr int KS = 64 + 8;    // Ks row stride (elements): 144 B, 16-byte aligned
@@ -25,34 +25,28 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_
     bf16_t *Vt = Ks + TKP * KS;              // [64][VS]
     bf16_t *Ot = Vt + 64 * VS;               // [waves][32][OS]: finished outputs of a wave's query tile, for row-wise stores
 
-    // nsplit workgroups share one (block, head): each stages all keys and values and takes every nsplit-th round of
-    // query tiles, so that no wave needs a second round at T = 197
     const int nb = n_blocks_dev ? min(*n_blocks_dev, n_blocks) : n_blocks;
-    const int part = blockIdx.x % nsplit, bh = blockIdx.x / nsplit;
-    const int b = bh / heads, hd = bh % heads;
+    const int b = blockIdx.x / heads, hd = blockIdx.x % heads;
     if (b >= nb) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lm = lane & 31, lh = lane >> 5;
     const size_t ld = (size_t)3 * D;
     const bf16_t *base = qkv + (size_t)b * T * ld + hd * 64;
-    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    const int nthreads = blockDim.x, nwaves = nthreads >> 6;
-    const int nq = (T + 31) / 32;
+    const int nthreads = blockDim.x;
 
-    // everything this thread will read from global memory is requested up front: its queries (at most two rounds),
-    // then its share of K (16-byte pieces) and of V (an 8 keys x 8 columns block, transposed in registers below)
-    bf16x8 qf[2][4];
+    // everything this thread will read from global memory is requested up front: its queries (wave w owns the 32-query
+    // tile w), then its share of K (16-byte pieces) and of V (an 8 keys x 8 columns block, transposed in registers below).
+    // Rows past T repeat row T - 1 (a load under a per-lane condition would be waited for on the spot): such keys are
+    // masked in the softmax and get probability 0, such queries are never stored
+    const int qs = wave, query = qs * 32 + lm;
+    bf16x8 qf[4];
 #pragma unroll
-    for (int rd = 0; rd < 2; ++rd) {
-        const int query = (part * nwaves + wave + rd * nwaves * nsplit) * 32 + lm;
-#pragma unroll
-        for (int ds = 0; ds < 4; ++ds) qf[rd][ds] = query < T ? *(const bf16x8 *)(base + (size_t)query * ld + ds * 16 + lh * 8) : zero8;
-    }
-    constexpr int NKP = NKT <= 4 ? 4 : NKT;        // K pieces (256 NKT) per thread: the workgroup has 64 min(NKT, 4) threads
+    for (int ds = 0; ds < 4; ++ds) qf[ds] = *(const bf16x8 *)(base + (size_t)min(query, T - 1) * ld + ds * 16 + lh * 8);
+    constexpr int NKP = 4;                         // K pieces (256 NKT) per thread: the workgroup has 64 NKT threads
     bf16x8 kp[NKP];
 #pragma unroll
     for (int i = 0; i < NKP; ++i) {
         const int v = tid + i * nthreads, key = v >> 3;
-        kp[i] = (v < TKP * 8 && key < T) ? *(const bf16x8 *)(base + (size_t)key * ld + D + (v & 7) * 8) : zero8;
+        kp[i] = *(const bf16x8 *)(base + (size_t)min(key, T - 1) * ld + D + (v & 7) * 8);
     }
     for (int blk = tid; blk < (TKP / 8) * 8; blk += nthreads) {
         const int cb = blk & 7, kb = blk >> 3;       // consecutive lanes: consecutive 16-byte pieces of a row of V
@@ -60,7 +54,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int key = kb * 8 + k;
-            vv[k] = key < T ? *(const bf16x8 *)(base + (size_t)key * ld + 2 * D + cb * 8) : zero8;
+            vv[k] = *(const bf16x8 *)(base + (size_t)min(key, T - 1) * ld + 2 * D + cb * 8);
         }
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
@@ -75,12 +69,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_
     }
     __syncthreads();
 
-#pragma unroll
-    for (int rd = 0; rd < 2; ++rd) {
-        const int qs = part * nwaves + wave + rd * nwaves * nsplit;
-        if (qs >= nq) break;
-        const int query = qs * 32 + lm;
-
+    {
         // S^T tile kt: rows = keys kt*32 + 8*(e/4) + 4*lh + e%4, column = this lane's query.  The K fragments of tile
         // kt + 1 are read while the MFMAs of tile kt run (the scheduling barriers pin that order)
         f32x16 s[NKT];
@@ -97,7 +86,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_
 #pragma unroll
             for (int e = 0; e < 16; ++e) s[kt][e] = 0.f;
 #pragma unroll
-            for (int ds = 0; ds < 4; ++ds) s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kt & 1][ds], qf[rd][ds], s[kt], 0, 0, 0);
+            for (int ds = 0; ds < 4; ++ds) s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kt & 1][ds], qf[ds], s[kt], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
 
@@ -182,7 +171,6 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16_t *qkv, bf16_
             const bf16x8 v = *(const bf16x8 *)(ot + row * OS + (lane & 7) * 8);
             if (qrow < T) *(bf16x8 *)(out + ((size_t)b * T + qrow) * D + hd * 64 + (lane & 7) * 8) = v;
         }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // reads done before the next round overwrites the tile
     }
 }
 
@@ -240,13 +228,10 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *qkv, float *
 template <int NKT>
 int launch_bf16(const void *qkv, void *out, int T, int D, int heads, int n_blocks, const int *n_blocks_dev, hipStream_t st)
 {
-    // up to 4 waves, one 32-query tile per wave and round (the score tile of a wave needs most of a SIMD's registers)
-    const int nq = (T + 31) / 32, waves = nq < 4 ? nq : 4;
-    // split (each half stages all keys and values, but no wave needs a second round) while the launch is small enough
-    // to leave CUs idle or single-occupied; large launches keep one workgroup per (block, head)
-    const int nsplit = nq > 4 && (long)n_blocks * heads <= 512 ? 2 : 1;
+    // one wave per 32-query tile (up to 7): two waves per SIMD share the softmax's vector work
+    const int waves = (T + 31) / 32;
     constexpr int TKP = NKT * 32;
-    constexpr int LDS = (TKP * 72 + 64 * (TKP + 8) + 4 * 32 * 72) * 2;
+    constexpr int LDS = (TKP * 72 + 64 * (TKP + 8) + NKT * 32 * 72) * 2;
     auto kern = attn_bf16_kernel<NKT>;
     if (LDS > 64 * 1024) {
         static bool attr_set = false;   // raising the dynamic LDS limit is a per-kernel, process-wide setting
@@ -255,8 +240,8 @@ int launch_bf16(const void *qkv, void *out, int T, int D, int heads, int n_block
             attr_set = true;
         }
     }
-    POLY_LAUNCH_SHMEM(POLY_STAGE_ATTN, kern, dim3((unsigned)(n_blocks * heads * nsplit)), dim3(64 * waves), LDS, st, (const bf16_t *)qkv, (bf16_t *)out, T, D,
-                      heads, n_blocks, n_blocks_dev, nsplit);
+    POLY_LAUNCH_SHMEM(POLY_STAGE_ATTN, kern, dim3((unsigned)(n_blocks * heads)), dim3(64 * waves), LDS, st, (const bf16_t *)qkv, (bf16_t *)out, T, D,
+                      heads, n_blocks, n_blocks_dev);
     return POLY_OK;
 }
 

@@ -278,10 +278,9 @@ extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *b
 
     if (R > 0) {
         POLY_TRY(launch_head(adapted ? w.xb : w.xa, adapted ? nullptr : w.frame_of_row, T, D, base->lnf_g, base->lnf_b, m->ln_eps,
-                             heads->head_w, heads->head_b, m->C, w.adapter_of_row, w.meta, R, out_logits, out_scores, dt, st));
+                             heads->head_w, heads->head_b, m->C, w.adapter_of_row, w.frame_of_row, heads->class_map, K, w.meta, R,
+                             out_logits, out_scores, out_merged, dt, st));
     }
-    if (out_merged)
-        POLY_TRY(launch_merge(out_scores, w.frame_of_row, w.adapter_of_row, heads->class_map, m->C, K, w.meta, F, R, out_merged, st));
     return POLY_OK;
 }
 

@@ -258,7 +258,6 @@ int launch_prep(const int32_t *row_offsets, const int32_t *adapter_ids, int F, i
 int launch_im2col(const void *frames, void *patches, int F, int H, int W, int p, int dtype, float *x, const float *cls, const float *pos,
                   int T_tok, int D, float *merged, size_t n_merged, hipStream_t st);
 int launch_head(const float *x, const int *src_block_of_row, int T, int D, const float *gain, const float *shift, float eps,
-                const void *head_w, const float *head_b, int C, const int *adapter_of_row, const PolyMeta *meta, int R_cap,
-                float *logits, float *scores, int dtype, hipStream_t st);
-int launch_merge(const float *scores, const int *frame_of_row, const int *adapter_of_row, const int32_t *class_map, int C, int K,
-                 const PolyMeta *meta, int F, int R_cap, float *merged, hipStream_t st);
+                const void *head_w, const float *head_b, int C, const int *adapter_of_row, const int *frame_of_row,
+                const int32_t *class_map, int K, const PolyMeta *meta, int R_cap, float *logits, float *scores, float *merged, int dtype,
+                hipStream_t st);

@@ -153,50 +153,81 @@ __global__ void shrink_f32_kernel(const float *X, int T, int K, const float *At,
     }
 }
 
-// ------------------------------------------------------------------ heads
-// One wave per row-block: z = LN(x[src][0][:]); logits = z H_k + hb_k; scores = sigmoid(logits).
-template <typename T>
+// ------------------------------------------------------------------ heads and merge to label space
+// One wave per row-block: z = LN(x[src][0][:]); logits = z H_k + hb_k; scores = sigmoid(logits); lane c
+// then folds class c into the frame's label vector.  Scores are in (0, 1): the order of positive floats
+// is the order of their bit patterns, so an integer atomic max merges overlapping adapters without
+// depending on arrival order.
+// NX = D/64 values of the row per lane (0: any D, strided loops).  With NX fixed the row, gain, shift and
+// the first head row are requested together and each later head row one class ahead of its use.
+template <typename T, int NX>
 __global__ __launch_bounds__(64) void head_kernel(const float *x, const int *src_block_of_row, int Tn, int D, const float *gain,
                                                   const float *shift, float eps, const T *head_w, const float *head_b, int C,
-                                                  const int *adapter_of_row, const PolyMeta *meta, float *logits, float *scores)
+                                                  const int *adapter_of_row, const int *frame_of_row, const int32_t *class_map,
+                                                  int K, const PolyMeta *meta, float *logits, float *scores, float *merged)
 {
     const int b = blockIdx.x;
     if (b >= meta->R) return;
     const int lane = threadIdx.x;
     const int src = src_block_of_row ? src_block_of_row[b] : b;
     const int k_ad = adapter_of_row[b];
+    const int fr = merged ? frame_of_row[b] : 0;
     const float *xr = x + (size_t)src * Tn * D;
-    float s = 0.f;
-    for (int k = lane; k < D; k += 64) s += xr[k];
-    const float mean = wave_sum(s) / D;
-    float v = 0.f;
-    for (int k = lane; k < D; k += 64) { const float d = xr[k] - mean; v += d * d; }
-    const float inv = rsqrtf(wave_sum(v) / D + eps);
-    for (int c = 0; c < C; ++c) {
-        const T *hw = head_w + ((size_t)k_ad * C + c) * D;
-        float a = 0.f;
-        for (int k = lane; k < D; k += 64) a = fmaf((xr[k] - mean) * inv * gain[k] + shift[k], to_f32(hw[k]), a);
-        a = wave_sum(a);
-        if (lane == 0) {
-            const float lg = a + head_b[k_ad * C + c];
-            if (logits) logits[(size_t)b * C + c] = lg;
-            scores[(size_t)b * C + c] = 1.0f / (1.0f + expf(-lg));
+    const int cl = lane < C ? lane : C - 1;
+    const float hb = head_b[k_ad * C + cl];
+    const int cls = merged ? class_map[k_ad * C + cl] : -1;
+    float mine = 0.f;
+    if constexpr (NX > 0) {
+        float xv[NX], g[NX], sh[NX], hw[NX], hn[NX];
+        const T *hk = head_w + (size_t)k_ad * C * D + lane;
+#pragma unroll
+        for (int i = 0; i < NX; ++i) xv[i] = xr[lane + 64 * i];
+#pragma unroll
+        for (int i = 0; i < NX; ++i) { g[i] = gain[lane + 64 * i]; sh[i] = shift[lane + 64 * i]; hw[i] = to_f32(hk[64 * i]); }
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < NX; ++i) s += xv[i];
+        const float mean = wave_sum(s) / D;
+        float v = 0.f;
+#pragma unroll
+        for (int i = 0; i < NX; ++i) { const float d = xv[i] - mean; v += d * d; }
+        const float inv = rsqrtf(wave_sum(v) / D + eps);
+#pragma unroll
+        for (int i = 0; i < NX; ++i) xv[i] = (xv[i] - mean) * inv * g[i] + sh[i];
+        for (int c = 0; c < C; ++c) {
+            const T *hnext = hk + (size_t)(c + 1 < C ? c + 1 : c) * D;
+#pragma unroll
+            for (int i = 0; i < NX; ++i) hn[i] = to_f32(hnext[64 * i]);
+            float a = 0.f;
+#pragma unroll
+            for (int i = 0; i < NX; ++i) a = fmaf(xv[i], hw[i], a);
+            a = wave_sum(a);
+            if (lane == c) mine = a;
+#pragma unroll
+            for (int i = 0; i < NX; ++i) hw[i] = hn[i];
+        }
+    } else {
+        float s = 0.f;
+        for (int k = lane; k < D; k += 64) s += xr[k];
+        const float mean = wave_sum(s) / D;
+        float v = 0.f;
+        for (int k = lane; k < D; k += 64) { const float d = xr[k] - mean; v += d * d; }
+        const float inv = rsqrtf(wave_sum(v) / D + eps);
+        for (int c = 0; c < C; ++c) {
+            const T *hw = head_w + ((size_t)k_ad * C + c) * D;
+            float a = 0.f;
+            for (int k = lane; k < D; k += 64) a = fmaf((xr[k] - mean) * inv * gain[k] + shift[k], to_f32(hw[k]), a);
+            a = wave_sum(a);
+            if (lane == c) mine = a;
         }
     }
-}
-
-// ------------------------------------------------------------------ merge to label space
-// scores are in (0, 1): the order of positive floats is the order of their bit patterns, so an integer
-// atomic max merges overlapping adapters without depending on arrival order
-__global__ void merge_kernel(const float *scores, const int *frame_of_row, const int *adapter_of_row, const int32_t *class_map,
-                             int C, int K, const PolyMeta *meta, float *merged)
-{
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= meta->R * C) return;
-    const int b = idx / C, c = idx % C;
-    const int cls = class_map[adapter_of_row[b] * C + c];
-    if (cls < 0 || cls >= K) return;
-    atomicMax((int *)(merged + (size_t)frame_of_row[b] * K + cls), __float_as_int(scores[idx]));
+    if (lane < C) {
+        const float lg = mine + hb;
+        const float sc = 1.0f / (1.0f + expf(-lg));
+        if (logits) logits[(size_t)b * C + lane] = lg;
+        scores[(size_t)b * C + lane] = sc;
+        if (cls >= 0 && cls < K) atomicMax((int *)(merged + (size_t)fr * K + cls), __float_as_int(sc));
+    }
 }
 
 }  // namespace
@@ -265,27 +296,37 @@ int launch_shrink(const void *X, int T, int K, const void *At, int r, int RP, fl
     return hip_ok();
 }
 
-int launch_head(const float *x, const int *src_block_of_row, int T, int D, const float *gain, const float *shift, float eps,
-                const void *head_w, const float *head_b, int C, const int *adapter_of_row, const PolyMeta *meta, int R_cap,
-                float *logits, float *scores, int dtype, hipStream_t st)
+template <typename T>
+static void launch_head_t(int nx, dim3 grid, hipStream_t st, const float *x, const int *src_block_of_row, int Tn, int D, const float *gain,
+                          const float *shift, float eps, const T *head_w, const float *head_b, int C, const int *adapter_of_row,
+                          const int *frame_of_row, const int32_t *class_map, int K, const PolyMeta *meta, float *logits, float *scores,
+                          float *merged)
 {
-    if (R_cap == 0) return POLY_OK;
-    if (dtype == POLY_BF16)
-        POLY_LAUNCH(POLY_STAGE_OTHER, head_kernel<bf16_t>, dim3(R_cap), dim3(64), st, x, src_block_of_row, T, D, gain, shift, eps,
-                           (const bf16_t *)head_w, head_b, C, adapter_of_row, meta, logits, scores);
-    else
-        POLY_LAUNCH(POLY_STAGE_OTHER, head_kernel<float>, dim3(R_cap), dim3(64), st, x, src_block_of_row, T, D, gain, shift, eps,
-                           (const float *)head_w, head_b, C, adapter_of_row, meta, logits, scores);
-    return hip_ok();
+#define HEAD_CASE(N)                                                                                                             \
+    case N:                                                                                                                      \
+        POLY_LAUNCH(POLY_STAGE_OTHER, (head_kernel<T, N>), grid, dim3(64), st, x, src_block_of_row, Tn, D, gain, shift, eps, head_w, head_b, \
+                    C, adapter_of_row, frame_of_row, class_map, K, meta, logits, scores, merged);                               \
+        break;
+    switch (nx) {
+        HEAD_CASE(1) HEAD_CASE(2) HEAD_CASE(3) HEAD_CASE(4) HEAD_CASE(6) HEAD_CASE(8) HEAD_CASE(12)
+        default: HEAD_CASE(0)
+    }
+#undef HEAD_CASE
 }
 
-int launch_merge(const float *scores, const int *frame_of_row, const int *adapter_of_row, const int32_t *class_map, int C, int K,
-                 const PolyMeta *meta, int F, int R_cap, float *merged, hipStream_t st)
+// heads, and the merge to the label space when merged is given (zeroed by the caller, F x K)
+int launch_head(const float *x, const int *src_block_of_row, int T, int D, const float *gain, const float *shift, float eps,
+                const void *head_w, const float *head_b, int C, const int *adapter_of_row, const int *frame_of_row,
+                const int32_t *class_map, int K, const PolyMeta *meta, int R_cap, float *logits, float *scores, float *merged, int dtype,
+                hipStream_t st)
 {
-    const size_t n = (size_t)F * K;
-    if (n == 0) return POLY_OK;
-    if (R_cap > 0)
-        POLY_LAUNCH(POLY_STAGE_OTHER, merge_kernel, dim3((R_cap * C + 255) / 256), dim3(256), st, scores, frame_of_row, adapter_of_row, class_map,
-                           C, K, meta, merged);
+    if (R_cap == 0) return POLY_OK;
+    const int nx = D % 64 == 0 ? D / 64 : 0;
+    if (dtype == POLY_BF16)
+        launch_head_t<bf16_t>(nx, dim3(R_cap), st, x, src_block_of_row, T, D, gain, shift, eps, (const bf16_t *)head_w, head_b, C,
+                              adapter_of_row, frame_of_row, class_map, K, meta, logits, scores, merged);
+    else
+        launch_head_t<float>(nx, dim3(R_cap), st, x, src_block_of_row, T, D, gain, shift, eps, (const float *)head_w, head_b, C,
+                             adapter_of_row, frame_of_row, class_map, K, meta, logits, scores, merged);
     return hip_ok();
 }

@@ -9,15 +9,18 @@
 // four, and x', the hidden activation and LayerNorm outputs never leave the chip.  Launch overhead and the cold
 // start of every kernel (inputs written by the previous kernel come from HBM) were a quarter of the layer time.
 //
-// Eight waves with two jobs, as in rowlin.hip / mlp.hip (a wave that issues a load into the saturated L2 path is
-// held at the issue stage, so the waves that compute issue none while they compute):
-//   waves 0-3 (2 x 2 over a 64 x 64 chunk): all MFMA work and the GELU;
-//   waves 4-7: the weight stream into a five-stage LDS ring (24 KB items), At_k / Bt_k of the block's adapter
-//             into LDS, and the residual stream: they hold x' (fp32, 4 threads per row) in registers from phase
-//             A to the end, do both LayerNorms on it and write x'' .
-// Phase boundaries pass a 64 x D fp32 tile through LDS (compute -> loaders); it takes the place of ring stages
-// 0-2, so every phase's stream starts in stage 3 and only two items of the next phase are prefetched across a
-// boundary.
+// Eight waves.  A wave that issues a load into the saturated L2 path is held at the issue stage, so the weight stream
+// has a wave of its own and the waves that compute issue no loads while they compute:
+//   waves 0-3 (2 x 2 over a 64 x 64 chunk): the MFMA work of A and C; in B the first product and the GELU;
+//   wave 4: the whole weight stream into a five-stage LDS ring (24 KB items);
+//   waves 5-7: in B the second product (wave 5 + j owns output columns 64 j .. 64 j + 63 of all 64 rows);
+//   waves 4-7 together: At_k / Bt_k of the block's adapter into LDS, and the residual stream: they hold x' (fp32,
+//             4 threads per row) in registers from phase A to the end, do both LayerNorms on it and write x''.
+// The loop of B is bound by the number of instructions a wave issues (a wave issues one every five cycles or so,
+// whatever the instruction; two waves on a SIMD issue twice as many), which is why its two products sit on
+// different waves: the GELU's arithmetic and the second product's operand reads are issued side by side.
+// Phase boundaries pass a 64 x D fp32 tile through LDS; it takes the place of ring stages 0-2, so every phase's
+// stream starts in stage 3 and only two items of the next phase are prefetched across a boundary.
 #include "poly_dev.h"
 #include "rowtile.h"
 
@@ -45,7 +48,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     constexpr int D = 64 * KT;
     constexpr int A_EL = (KT < 2 ? 2 : KT) * 64 * 64;   // activation rows (KT tiles of [64][64]) / Bt_k / the two hidden tiles
     constexpr int IT_EL = KT * 64 * 64;          // one stream item: KT tiles of [64][64]
-    constexpr int NLD = 2 * KT;                  // loads per loader wave and item: 16 rows of each tile, 8 rows per load
+    constexpr int NLD = 8 * KT;                  // loads per item (all by wave 4): 64 rows of each tile, 8 rows per load
     constexpr int NV = D / 16;                   // 16-byte pieces of an fp32 row per loader thread (4 threads per row)
     constexpr int XSTRIDE = D * 4 + 16;          // bytes per row of the fp32 hand-over tile
     extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
@@ -81,8 +84,8 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     const int PC = HAS_QKV ? ((PB + NQ + 1) / 5) * 5 + 3 : 0;       // smallest position >= PB + NQ that is 3 mod 5
     const int NI = NA + NQ + (HAS_QKV ? nchq : 0);                  // items, numbered in order
     auto pos_of = [&](int i) { return i < NA ? i : (i < NA + NQ ? PB + (i - NA) : PC + (i - NA - NQ)); };
-    // loader wave w loads rows 16w .. 16w + 15 of each of the item's KT tiles, 8 rows (1 KB) per load; a row's 128 bytes
-    // land in lane order, the tile swizzle is applied by permuting the 16-byte pieces on the global side
+    // wave 4 loads each of the item's KT tiles, 8 rows (1 KB) per load; a row's 128 bytes land in lane order, the tile
+    // swizzle is applied by permuting the 16-byte pieces on the global side
     auto issue_item = [&](int i) {
         bf16_t *st = Ws + (pos_of(i) % LY_NS) * IT_EL;
         const bf16_t *base;
@@ -96,14 +99,16 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             else { base = a.W2t + (size_t)c * 64; rstride = Dm; tstride = 64 * Dm; }                      // tile t: output columns 64 t ..
             nrow = 64;
         } else { const int c = i - NA - NQ; base = a.Wqt + (size_t)c * 64 * D; rstride = D; tstride = 64; nrow = Nq - c * 64; }
+        // row 8 g + lr of a tile: its 16-byte pieces are permuted by (row >> 1) & 7 = 4 (g & 1) + (lr >> 1).  Every matrix
+        // here has a multiple of 64 rows, so no row of a tile is past its end.
+        const unsigned rb = rstride * 2;
+        const unsigned e0 = lr * rb + ((((lane & 7) ^ (lr >> 1))) << 4), e1 = lr * rb + ((((lane & 7) ^ (4 + (lr >> 1)))) << 4);
+        const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(st));
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int row = lw * 16 + half * 8 + lr;
-            const unsigned off = (min(row, nrow - 1) * rstride + (((lane & 7) ^ ((row >> 1) & 7)) << 3)) * 2;   // rows past the matrix repeat its last row
-#pragma unroll
-            for (int t = 0; t < KT; ++t)
-                glds16_s(base + (size_t)t * tstride, off, __builtin_amdgcn_readfirstlane(lds_addr_of(st + t * 4096 + (lw * 16 + half * 8) * 64)));
-        }
+        for (int t = 0; t < KT; ++t)
+            glds16_tile8(base + (size_t)t * tstride, lds0 + t * 8192, e0, e1 + 8 * rb, e0 + 16 * rb, e1 + 24 * rb, e0 + 32 * rb, e1 + 40 * rb,
+                         e0 + 48 * rb, e1 + 56 * rb);
+        (void)nrow;
     };
     // At_k [r][D] -> at_s, one rank row per load (24 * KT / 3 lanes), rows LY_AT_STRIDE elements apart
     auto issue_at = [&](const bf16_t *At_k, int r) {
@@ -163,12 +168,16 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     // (the positions that a hand-over tile is about to use).
     int last = -1;
     auto refill = [&](int cpos, int cap) {
-        while (last + 1 < NI && pos_of(last + 1) <= min(cpos + LY_NS, cap)) issue_item(++last);
+        while (last + 1 < NI && pos_of(last + 1) <= min(cpos + LY_NS, cap)) {
+            ++last;
+            if (wave == 4) issue_item(last);
+        }
     };
-    auto wait_item = [&](int need) {             // item `need` has landed; newer ones may stay in flight (loads complete in issue order)
-        const int ahead = last - need;
-        if (ahead >= 3) rl_wait_barrier<3 * NLD>();
-        else if (ahead == 2) rl_wait_barrier<2 * NLD>();
+    // item `need` has landed; newer ones may stay in flight (loads complete in issue order; the counter holds 63).
+    // Waves 5-7 have no part in the stream: whatever else they requested has landed after this.
+    auto wait_item = [&](int need) {
+        const int ahead = wave == 4 ? last - need : 0;
+        if (ahead >= 2) rl_wait_barrier<2 * NLD>();
         else if (ahead == 1) rl_wait_barrier<NLD>();
         else rl_wait_barrier<0>();
     };
@@ -339,19 +348,76 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     }
 
     // ================================================================ phase B: y = GELU(LayerNorm2(x') W1 + b1) W2
-    f32x16 y[KT];                                // rows wr*32 + lm, columns wc*32*KT + 32 p + ..
+    // Step h (0 .. nch + 1), one barrier each:
+    //   waves 0-3: hb[h & 1] = LayerNorm2(x') W1 rows of chunk h; hidden tile of chunk h - 1 = GELU(hb[(h - 1) & 1] + b1),
+    //              a quarter of the GELU's arithmetic between the MFMAs of each K step;
+    //   waves 5-7: y += hidden(chunk h - 2) W2 slice;   wave 4: the stream.
+    bf16_t *Hs = As;                             // hidden tiles [64 rows][64 columns of a chunk], chunk c in tile c & 1 (As is dead
+                                                 // once every wave has its fa: the barrier of step 0 comes before the first write)
+    using T_ = std::true_type;
+    using F_ = std::false_type;
     if (loader) {
-        auto need_at = [&](int h) { return h < 2 ? h : min(2 * h - 1, NQ - 1); };
+        const int j = wave - 5;                  // waves 5-7: output columns 64 j .. 64 j + 63, rows rt*32 + lm, as y[rt][ct]
+        const bool second = j >= 0 && j < KT;
+        f32x16 y[2][2];
+        if (second) {
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const f32x4 b = *(const f32x4 *)(b2_s + 64 * j + ct * 32 + 8 * g4 + 4 * lh);   // the accumulators start from b2
+#pragma unroll
+                    for (int z = 0; z < 4; ++z) y[0][ct][4 * g4 + z] = y[1][ct][4 * g4 + z] = b[z];
+                }
+        }
+        // newest item that step h reads: W1(h) while there is one, then the last two slices of W2 (an item counts as consumed,
+        // and its ring position as free, one barrier after the step that reads it)
+        auto need_at = [&](int h) { return h < 2 ? h : (h < nch ? 2 * h - 1 : NQ - 2 + (h - nch)); };
         for (int h = 0; h < nch + 2; ++h) {
             wait_item(NA + need_at(h));
             if (h == 0) gelu_tab_build(gelu_s, lt, 256);   // every computing wave holds its fragments of LayerNorm2(x') by now; first used in step 1
             refill(h >= 1 ? PB + need_at(h - 1) : PB - 1, capB);
+            if (second && h >= 2) {
+                const bf16_t *s2 = Ws + ((PB + (h == nch + 1 ? NQ - 1 : 2 * h - 2)) % LY_NS) * IT_EL + j * 4096;   // W2(h - 2), columns 64 j ..
+                const bf16_t *Hr = Hs + (h & 1) * 4096;                                                            // chunk h - 2
+                bf16x8 fh[2][2], f2[2][2];
+                auto load = [&](int kk, int s) {
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        fh[s][t] = *(const bf16x8 *)(Hr + tile_off(t * 32 + lm, 2 * kk + lh));
+                        f2[s][t] = *(const bf16x8 *)(s2 + tile_off(t * 32 + lm, 2 * kk + lh));
+                    }
+                };
+                load(0, 0);
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    if (kk < 3) load(kk + 1, (kk + 1) & 1);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                        for (int ct = 0; ct < 2; ++ct)
+                            y[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[kk & 1][ct], fh[kk & 1][rt], y[rt][ct], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
         }
         LY_TS(8);
         rl_wait_barrier<0>();                                                   // Be: every item of B is consumed
         if (lora_q) issue_at(a.Aqt + (size_t)k_ad * a.r * D, a.r);              // before the chunks of C, whose wait then covers it
         refill(HAS_QKV ? PC - 1 : 0, HAS_QKV ? PC + 1 : -1);                    // (the tile still needs stages 0-2)
-        asm volatile("s_barrier" ::: "memory");                                 // By: the y tile is complete
+        if (second) {
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt) {
+                char *trow = xtile + (rt * 32 + lm) * XSTRIDE + (64 * j + 4 * lh) * 4;
+#pragma unroll
+                for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4)
+                        *(f32x4 *)(trow + (ct * 32 + 8 * g4) * 4) = f32x4{y[rt][ct][4 * g4], y[rt][ct][4 * g4 + 1], y[rt][ct][4 * g4 + 2], y[rt][ct][4 * g4 + 3]};
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // By: the y tile is complete
         float *dst = a.x_out + ((size_t)ob * a.T + t0 + (lt >> 2)) * D + 4 * (lt & 3);
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
@@ -362,103 +428,66 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         LY_TS(9);
     } else {
         load_fa();
-        f32x16 hcur, hnext;                      // first product of chunks h - 1 / h: row lm, columns wc*32 + 8*(e/4) + 4*lh + e%4
-#pragma unroll
-        for (int p = 0; p < KT; ++p)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const f32x4 b = *(const f32x4 *)(b2_s + wc * 32 * KT + p * 32 + 8 * g4 + 4 * lh);   // the accumulators start from b2
-#pragma unroll
-                for (int z = 0; z < 4; ++z) y[p][4 * g4 + z] = b[z];
-            }
-#pragma unroll
-        for (int e = 0; e < 16; ++e) hcur[e] = hnext[e] = 0.f;
-        bf16_t *Hs = As;                         // hidden tiles [64 rows][64 columns of a chunk], chunk c in tile c & 1 (As is dead
-                                                 // once every wave has its fa: the barrier of step 0 comes before the first write)
-        // step h: d1: hnext = LayerNorm2(x') W1 rows of chunk h; dg: hidden tile of chunk h - 1 = GELU(hcur + b1);
-        // d2: y += hidden(chunk h - 2) W2 slice, with a quarter of the GELU arithmetic between the MFMAs of each K step
-        auto compute_step = [&](auto D1, auto DG, auto D2, int h) {
-            constexpr bool d1 = decltype(D1)::value, dg = decltype(DG)::value, d2 = decltype(D2)::value;
+        f32x16 hb[2];                            // first product of chunks h / h - 1: row lm, columns wc*32 + 8*(e/4) + 4*lh + e%4
+        auto first_step = [&](auto D1, auto DG, auto PAR, int h) {
+            constexpr bool d1 = decltype(D1)::value, dg = decltype(DG)::value;
+            constexpr int par = decltype(PAR)::value ? 1 : 0;          // h & 1
+            f32x16 &hout = hb[par], &hin = hb[par ^ 1];
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            const bf16_t *s2 = Ws + ((PB + (h == nch + 1 ? NQ - 1 : 2 * h - 2)) % LY_NS) * IT_EL;   // W2(h - 2)
             const bf16_t *s1 = Ws + ((PB + (h < 2 ? h : 2 * h - 1)) % LY_NS) * IT_EL;               // W1(h)
-            const bf16_t *Hr = Hs + (h & 1) * 4096;                                                  // chunk h - 2
             bf16_t *Hw = Hs + ((h - 1) & 1) * 4096;                                                  // chunk h - 1
-            bf16x8 fh[2], f2[2][KT], f1[2][KT];
+            bf16x8 f1[2][KT];
             f32x4 b[4];
             auto load = [&](int kk, int s) {
-                if (d2) {
-                    fh[s] = *(const bf16x8 *)(Hr + tile_off(wr * 32 + lm, 2 * kk + lh));
 #pragma unroll
-                    for (int p = 0; p < KT; ++p) {
-                        const int ncol = wc * 32 * KT + p * 32;   // first of this piece's 32 output columns
-                        f2[s][p] = *(const bf16x8 *)(s2 + (ncol >> 6) * 4096 + tile_off((ncol & 63) + lm, 2 * kk + lh));
-                    }
-                }
-                if (d1) {
-#pragma unroll
-                    for (int kt = 0; kt < KT; ++kt) f1[s][kt] = *(const bf16x8 *)(s1 + kt * 4096 + tile_off(wc * 32 + lm, 2 * kk + lh));
-                }
+                for (int kt = 0; kt < KT; ++kt) f1[s][kt] = *(const bf16x8 *)(s1 + kt * 4096 + tile_off(wc * 32 + lm, 2 * kk + lh));
             };
             if (dg) {
                 const float *bp = b1_s + (h - 1) * 64 + wc * 32 + 4 * lh;
 #pragma unroll
                 for (int g4 = 0; g4 < 4; ++g4) b[g4] = *(const f32x4 *)(bp + 8 * g4);
             }
-            load(0, 0);
+            if (d1) load(0, 0);
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                if (kk < 3) load(kk + 1, (kk + 1) & 1);
+                if (d1 && kk < 3) load(kk + 1, (kk + 1) & 1);
                 __builtin_amdgcn_sched_barrier(0);
-                if (d2) {
-#pragma unroll
-                    for (int p = 0; p < KT; ++p) y[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[kk & 1][p], fh[kk & 1], y[p], 0, 0, 0);
-                }
                 if (d1) {
 #pragma unroll
-                    for (int kt = 0; kt < KT; ++kt) hnext = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[kk & 1][kt], fa[kt * 4 + kk], hnext, 0, 0, 0);
+                    for (int kt = 0; kt < KT; ++kt) {
+                        const f32x16 z16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                        hout = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[kk & 1][kt], fa[kt * 4 + kk], kk == 0 && kt == 0 ? z16 : hout, 0, 0, 0);
+                    }
                 }
                 if (dg) {
-                    // a quarter of the chunk's GELU per K step, through the Phi table (fewer instructions than the polynomial:
-                    // this loop is bound by the number of instructions the wave issues)
-                    const f32x4 v = gelu_tab4(f32x4{hcur[4 * kk], hcur[4 * kk + 1], hcur[4 * kk + 2], hcur[4 * kk + 3]} + b[kk], gelu_s);
+                    // a quarter of the chunk's GELU per K step, through the Phi table (fewer instructions than the polynomial)
+                    const f32x4 v = gelu_tab4(f32x4{hin[4 * kk], hin[4 * kk + 1], hin[4 * kk + 2], hin[4 * kk + 3]} + b[kk], gelu_s);
                     const bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
                     *(bf16x4 *)(Hw + tile_off(wr * 32 + lm, 4 * wc + kk) + 4 * lh) = o;
                 }
-                if ((d1 || d2) && dg) {
+                if (d1 && dg) {
                     // one MFMA, then a share of the vector work, so that the vector work is issued while an MFMA runs
-                    constexpr int NM = (d1 ? KT : 0) + (d2 ? KT : 0);
 #pragma unroll
-                    for (int i = 0; i < NM; ++i) {
+                    for (int i = 0; i < KT; ++i) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, (40 + NM - 1) / NM, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, (40 + KT - 1) / KT, 0);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (d1) {
-                hcur = hnext;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) hnext[e] = 0.f;
-            }
         };
-        using T_ = std::true_type;
-        using F_ = std::false_type;
-        compute_step(T_{}, F_{}, F_{}, 0);
-        compute_step(T_{}, T_{}, F_{}, 1);
-        for (int h = 2; h < nch; ++h) compute_step(T_{}, T_{}, T_{}, h);
-        compute_step(F_{}, T_{}, T_{}, nch);
-        compute_step(F_{}, F_{}, T_{}, nch + 1);
+        first_step(T_{}, F_{}, F_{}, 0);
+        for (int h = 1; h < nch; ++h) {
+            if (h & 1) first_step(T_{}, T_{}, T_{}, h);
+            else first_step(T_{}, T_{}, F_{}, h);
+        }
+        if (nch & 1) first_step(F_{}, T_{}, T_{}, nch);
+        else first_step(F_{}, T_{}, F_{}, nch);
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // step nch + 1: the other waves' last product
         LY_TS(8);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // Be: the ring positions of B are consumed
-        char *trow = xtile + (wr * 32 + lm) * XSTRIDE + (wc * 32 * KT + 4 * lh) * 4;
-#pragma unroll
-        for (int p = 0; p < KT; ++p)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4)
-                *(f32x4 *)(trow + (p * 32 + 8 * g4) * 4) = f32x4{y[p][4 * g4], y[p][4 * g4 + 1], y[p][4 * g4 + 2], y[p][4 * g4 + 3]};
         LY_TS(9);
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // By
+        asm volatile("s_barrier" ::: "memory");                                 // By
     }
     if (!HAS_QKV) return;
 

@@ -17,6 +17,23 @@ __device__ __forceinline__ void glds16_s(const void *sbase, unsigned voff, unsig
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase) : "memory", "m0");
 }
+// eight such loads in a row, one wave filling a whole [64][64] bf16 tile: load g takes the per-lane byte offset voff[g]
+// from the uniform base and lands at lds_byte_addr + 1024 g + 16 * lane.  Three instructions per load (the LDS
+// position advances inside M0), for a wave whose only job is to keep the stream going.
+__device__ __forceinline__ void glds16_tile8(const void *sbase, unsigned lds_byte_addr, unsigned v0, unsigned v1, unsigned v2, unsigned v3,
+                                             unsigned v4, unsigned v5, unsigned v6, unsigned v7)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %1\n\t"
+                 "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, %1\n\t"
+                 "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, %1\n\t"
+                 "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %5, %1\n\t"
+                 "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %6, %1\n\t"
+                 "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %7, %1\n\t"
+                 "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %8, %1\n\t"
+                 "s_add_u32 m0, m0, 0x400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %9, %1" ::"s"(lds_byte_addr),
+                 "s"(sbase), "v"(v0), "v"(v1), "v"(v2), "v"(v3), "v"(v4), "v"(v5), "v"(v6), "v"(v7)
+                 : "memory", "m0", "scc");
+}
 __device__ __forceinline__ unsigned lds_addr_of(const void *p)
 {
     return (unsigned)(size_t)(const __attribute__((address_space(3))) void *)p;

@@ -51,6 +51,7 @@ def test_small_models_all_target_sets(dtype, targets, L0, r):
     (128, 2, 256, 64, 12, 3, 0),    # rank 12: the second half of the expand operand is partly empty
     (192, 3, 768, 40, 8, 3, 2),     # DeiT-tiny widths, T = 26, fan-out at layer 2
     (192, 3, 320, 72, 16, 2, 0),    # adapters on proj only, Dm = 5 chunks, T = 82
+    (128, 2, 384, 64, 8, 3, 0),     # Dm = 6 chunks: the last feed-forward item and the second qkv item share a stage of the weight ring
 ])
 def test_row_kernels_all_widths(D, heads, Dm, hw, r, targets, L0):
     """bf16 models whose layers run in the fused row kernels (no adapters on fc1 / fc2): every tile width, ragged tiles."""

@@ -300,7 +300,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
                 if (s == 0 && lora_p) issue_bt(a.Bpt + (size_t)k_ad * D * a.r, D, a.r);     // the computing waves hold their fragments by now
                 refill(2 * s - 1, capA);
             }
-            rl_wait_barrier<0>();                                               // Bf: Bt_k has landed
+            wait_item(NA - 1);                                                  // Bf: Bt_k has landed (it is older than the items still in flight)
             LY_TS(5);
             asm volatile("s_barrier" ::: "memory");                             // Bs: the tile is complete
             LY_TS(6);
@@ -376,6 +376,9 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         for (int h = 0; h < nch + 2; ++h) {
             wait_item(NA + need_at(h));
             if (h == 0) gelu_tab_build(gelu_s, lt, 256);   // every computing wave holds its fragments of LayerNorm2(x') by now; first used in step 1
+            // At_k of the qkv linear: at_s is idle since the shrink of phase A, and a request made here does not queue up
+            // behind the first chunks of C
+            if (h == 1 && lora_q) issue_at(a.Aqt + (size_t)k_ad * a.r * D, a.r);
             refill(h >= 1 ? PB + need_at(h - 1) : PB - 1, capB);
             if (second && h >= 2) {
                 const bf16_t *s2 = Ws + ((PB + (h == nch + 1 ? NQ - 1 : 2 * h - 2)) % LY_NS) * IT_EL + j * 4096;   // W2(h - 2), columns 64 j ..
@@ -403,8 +406,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             }
         }
         LY_TS(8);
-        rl_wait_barrier<0>();                                                   // Be: every item of B is consumed
-        if (lora_q) issue_at(a.Aqt + (size_t)k_ad * a.r * D, a.r);              // before the chunks of C, whose wait then covers it
+        wait_item(NA + NQ - 1);                                                 // Be: every item of B is consumed
         refill(HAS_QKV ? PC - 1 : 0, HAS_QKV ? PC + 1 : -1);                    // (the tile still needs stages 0-2)
         if (second) {
 #pragma unroll

@@ -100,6 +100,21 @@ template <int KT> __device__ __forceinline__ void ln_gb_store(f32x4 v, float *gb
 {
     if (tid < 32 * KT) *(f32x4 *)(gb_s + 4 * tid) = v;
 }
+// sum over the TPR (4 or 8) adjacent lanes that share a row, in every one of them: data-parallel-primitive moves inside
+// the quad (lane ^ 1, lane ^ 2) and across the two quads of eight lanes (mirror: every lane of a quad holds the quad's sum by
+// then) -- a shuffle through the LDS crossbar costs a hundred-odd cycles per step
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int TPR> __device__ __forceinline__ float row_group_sum(float s)
+{
+    static_assert(TPR == 4 || TPR == 8, "threads per row");
+    s += dpp_move<0xB1>(s);                      // quad_perm [1, 0, 3, 2]
+    s += dpp_move<0x4E>(s);                      // quad_perm [2, 3, 0, 1]
+    if (TPR == 8) s += dpp_move<0x141>(s);       // row_half_mirror
+    return s;
+}
 template <int KT, int TPR>
 __device__ __forceinline__ void ln_finish(const f32x4 (&v)[64 * KT / TPR / 4], const float *gb_s, float eps, bf16_t *As, int tid)
 {
@@ -108,16 +123,14 @@ __device__ __forceinline__ void ln_finish(const f32x4 (&v)[64 * KT / TPR / 4], c
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
-#pragma unroll
-    for (int m = 1; m < TPR; m <<= 1) s += __shfl_xor(s, m, 64);
+    s = row_group_sum<TPR>(s);
     const float mean = s * (1.0f / K);
     float q = 0.f;
 #pragma unroll
     for (int i = 0; i < NV; ++i)
 #pragma unroll
         for (int z = 0; z < 4; ++z) { const float d = v[i][z] - mean; q = fmaf(d, d, q); }
-#pragma unroll
-    for (int m = 1; m < TPR; m <<= 1) q += __shfl_xor(q, m, 64);
+    q = row_group_sum<TPR>(q);
     const float inv = rsqrtf(q * (1.0f / K) + eps), nmi = -mean * inv;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {

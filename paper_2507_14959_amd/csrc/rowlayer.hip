@@ -29,6 +29,7 @@
 // phase timestamps for tuning; a test harness defines the macros before including this file
 #ifndef LY_TS
 #define LY_TS(i)
+#define LY_TSS(slot)
 #define LY_TS_END
 #define LY_TS_BYTES 0
 #endif
@@ -71,34 +72,31 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     const bool loader = wave >= 4;
     const int wr = (wave >> 1) & 1, wc = wave & 1, lm = lane & 31, lh = lane >> 5;
     const int lw = wave & 3, lr = lane >> 3, lt = tid & 255;
-    const int Dm = a.Dm, nch = Dm >> 6, NQ = 2 * nch;
+    const int Dm = a.Dm, nch = Dm >> 6;
     const int Nq = 3 * D, nchq = (Nq + 63) / 64;
     const int rows = min(64, a.T - t0);
 
-    // ---- the stream: positions in the ring.  Phase A: Wp chunk c at position c.  Phase B: item j at PB + j, in order
-    // of use (step h needs W2's slice of chunk h - 2 and W1's rows of chunk h):
-    //   j = 0, 1: W1(0), W1(1);  j = 2, 3: W2(0), W1(2);  j = 4, 5: W2(1), W1(3); ... ; last two: W2(nch-2), W2(nch-1).
-    // Phase C: Wq chunk c at PC + c.  Stage = position % 5; PB and PC are 3 mod 5 (see the head of this file).
+    // ---- the stream.  Items (KT tiles each), in order: phase A: Wp chunk c (stage c); phase B: W1's rows of chunk c, for
+    // the first product, in the four stages 0-3 (stage (SB0 + c) % 4; SB0 = 3 when A comes first, whose hand-over tile takes
+    // stages 0-2); phase C: Wq chunk c at position PC + c (stage = position % 5, PC = 3 mod 5).  The slices of W2 do not pass
+    // through the ring: each wave of the second product keeps its own tile of the current slice in stage 4 and requests the
+    // next one itself (see phase B).
     const int NA = HAS_PROJ ? KT : 0;
-    const int PB = HAS_PROJ ? 3 : 0;
-    const int PC = HAS_QKV ? ((PB + NQ + 1) / 5) * 5 + 3 : 0;       // smallest position >= PB + NQ that is 3 mod 5
-    const int NI = NA + NQ + (HAS_QKV ? nchq : 0);                  // items, numbered in order
-    auto pos_of = [&](int i) { return i < NA ? i : (i < NA + NQ ? PB + (i - NA) : PC + (i - NA - NQ)); };
+    constexpr int SB0 = HAS_PROJ ? 3 : 0;
+    const int PC = 8;
+    const int NI = NA + nch + (HAS_QKV ? nchq : 0);                 // items, numbered in order
+    // ring position for the items of A and C; those of B are requested explicitly (never by refill)
+    auto pos_of = [&](int i) { return i < NA ? i : (i < NA + nch ? 1 << 20 : PC + (i - NA - nch)); };
     // wave 4 loads each of the item's KT tiles, 8 rows (1 KB) per load; a row's 128 bytes land in lane order, the tile
     // swizzle is applied by permuting the 16-byte pieces on the global side
     auto issue_item = [&](int i) {
-        bf16_t *st = Ws + (pos_of(i) % LY_NS) * IT_EL;
         const bf16_t *base;
-        int rstride, tstride, nrow;                       // elements between rows / between tiles; rows that exist
-        if (i < NA) { base = a.Wpt + (size_t)i * 64 * D; rstride = D; tstride = 64; nrow = D - i * 64; }
-        else if (i < NA + NQ) {
-            const int q = i - NA;
-            const bool second = q >= 2 && ((q & 1) == 0 || q == NQ - 1);
-            const int c = q < 2 ? q : (second ? (q == NQ - 1 ? nch - 1 : (q >> 1) - 1) : (q + 1) >> 1);
-            if (!second) { base = a.W1t + (size_t)c * 64 * D; rstride = D; tstride = 64; }              // tile t: k = 64 t ..
-            else { base = a.W2t + (size_t)c * 64; rstride = Dm; tstride = 64 * Dm; }                      // tile t: output columns 64 t ..
-            nrow = 64;
-        } else { const int c = i - NA - NQ; base = a.Wqt + (size_t)c * 64 * D; rstride = D; tstride = 64; nrow = Nq - c * 64; }
+        int stage;
+        if (i < NA) { base = a.Wpt + (size_t)i * 64 * D; stage = i; }
+        else if (i < NA + nch) { const int c = i - NA; base = a.W1t + (size_t)c * 64 * D; stage = (SB0 + c) & 3; }
+        else { const int c = i - NA - nch; base = a.Wqt + (size_t)c * 64 * D; stage = (PC + c) % LY_NS; }
+        bf16_t *st = Ws + stage * IT_EL;
+        const int rstride = D, tstride = 64;              // elements between rows / between tiles (tile t: k = 64 t ..)
         // row 8 g + lr of a tile: its 16-byte pieces are permuted by (row >> 1) & 7 = 4 (g & 1) + (lr >> 1).  Every matrix
         // here has a multiple of 64 rows, so no row of a tile is past its end.
         const unsigned rb = rstride * 2;
@@ -108,7 +106,6 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         for (int t = 0; t < KT; ++t)
             glds16_tile8(base + (size_t)t * tstride, lds0 + t * 8192, e0, e1 + 8 * rb, e0 + 16 * rb, e1 + 24 * rb, e0 + 32 * rb, e1 + 40 * rb,
                          e0 + 48 * rb, e1 + 56 * rb);
-        (void)nrow;
     };
     // At_k [r][D] -> at_s, one rank row per load (24 * KT / 3 lanes), rows LY_AT_STRIDE elements apart
     auto issue_at = [&](const bf16_t *At_k, int r) {
@@ -170,7 +167,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     auto refill = [&](int cpos, int cap) {
         while (last + 1 < NI && pos_of(last + 1) <= min(cpos + LY_NS, cap)) {
             ++last;
-            if (wave == 4) issue_item(last);
+            if (wave == 4) { issue_item(last); LY_TSS(128 + last); }
         }
     };
     // item `need` has landed; newer ones may stay in flight (loads complete in issue order; the counter holds 63).
@@ -181,14 +178,18 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         else if (ahead == 1) rl_wait_barrier<NLD>();
         else rl_wait_barrier<0>();
     };
-    const int capA = PB + 1, capB = HAS_QKV ? PC + 1 : 1 << 30;   // stages 0-2 are kept free for the tile at the end of A / B
+    auto issue_next = [&]() {                    // the next item, whatever its position (the caller knows its stage is free)
+        ++last;
+        if (wave == 4) { issue_item(last); LY_TSS(128 + last); }
+    };
 
     if (loader) {
         if (!res_early) load_res(a.res_block_of_out[ob]);
         // the first items only (all of phase A, or two of B) -- the rows above are still on their way and would be slowed
         // down by more.  At_k first: the wait for the first chunks then covers it (loads complete in issue order).
         if (lora_p) issue_at(a.Apt + (size_t)k_ad * a.r * D, a.r);
-        refill(-1, HAS_PROJ ? KT - 1 : 1);
+        if (HAS_PROJ) refill(-1, KT - 1);
+        else { issue_next(); issue_next(); }       // (nch >= 2)
     } else {
         // prologue of the computing waves: what they requested -> LDS
         if (HAS_PROJ) {
@@ -298,7 +299,8 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             for (int s = 0; s < SA; ++s) {
                 wait_item(min(2 * s + 1, KT - 1));
                 if (s == 0 && lora_p) issue_bt(a.Bpt + (size_t)k_ad * D * a.r, D, a.r);     // the computing waves hold their fragments by now
-                refill(2 * s - 1, capA);
+                refill(2 * s - 1, 1 << 20);
+                if (s == 0) issue_next();                                           // W1's first rows: stage 3 is free all through A
             }
             wait_item(NA - 1);                                                  // Bf: Bt_k has landed (it is older than the items still in flight)
             LY_TS(5);
@@ -370,28 +372,47 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
                     for (int z = 0; z < 4; ++z) y[0][ct][4 * g4 + z] = y[1][ct][4 * g4 + z] = b[z];
                 }
         }
-        // newest item that step h reads: W1(h) while there is one, then the last two slices of W2 (an item counts as consumed,
-        // and its ring position as free, one barrier after the step that reads it)
-        auto need_at = [&](int h) { return h < 2 ? h : (h < nch ? 2 * h - 1 : NQ - 2 + (h - nch)); };
+        // this wave's tile of W2's slice c (output columns 64 j .., hidden columns 64 c ..) -> its 8 KB of stage 4
+        bf16_t *w2_s = Ws + 4 * IT_EL + (second ? j : 0) * 4096;
+        auto issue_w2 = [&](int c) {
+            const unsigned rb = Dm * 2;
+            const unsigned e0 = lr * rb + ((((lane & 7) ^ (lr >> 1))) << 4), e1 = lr * rb + ((((lane & 7) ^ (4 + (lr >> 1)))) << 4);
+            glds16_tile8(a.W2t + (size_t)j * 64 * Dm + (size_t)c * 64, __builtin_amdgcn_readfirstlane(lds_addr_of(w2_s)), e0, e1 + 8 * rb,
+                         e0 + 16 * rb, e1 + 24 * rb, e0 + 32 * rb, e1 + 40 * rb, e0 + 48 * rb, e1 + 56 * rb);
+        };
         for (int h = 0; h < nch + 2; ++h) {
-            wait_item(NA + need_at(h));
+            // wave 4: W1(h) has landed (later chunks may be in flight).  Waves 5-7 keep their own loads in flight across the
+            // barrier and wait for them below.
+            if (wave == 4) wait_item(NA + min(h, nch - 1));
+            else asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            LY_TSS(32 * (wave - 2) + 2 * h);
             if (h == 0) gelu_tab_build(gelu_s, lt, 256);   // every computing wave holds its fragments of LayerNorm2(x') by now; first used in step 1
             // At_k of the qkv linear: at_s is idle since the shrink of phase A, and a request made here does not queue up
             // behind the first chunks of C
             if (h == 1 && lora_q) issue_at(a.Aqt + (size_t)k_ad * a.r * D, a.r);
-            refill(h >= 1 ? PB + need_at(h - 1) : PB - 1, capB);
+            // the stream of W1: chunks 1-3 into stages 0-2 once the hand-over tile is dead, then chunk h + 3 into the stage
+            // that chunk h - 1 has left; the first chunk of C once W1 is through (stage 3; the second one needs stage 4)
+            if (h == 0) { while (last + 1 < NA + min(nch, 4)) issue_next(); }
+            else if (last + 1 < NA + nch) issue_next();
+            else if (HAS_QKV && h == nch && last + 1 == NA + nch) issue_next();
+            if (second && h == 0) issue_w2(0);
             if (second && h >= 2) {
-                const bf16_t *s2 = Ws + ((PB + (h == nch + 1 ? NQ - 1 : 2 * h - 2)) % LY_NS) * IT_EL + j * 4096;   // W2(h - 2), columns 64 j ..
+                // The slice of W2 does not pass through the shared ring: this wave's tile of it landed in its own 8 KB (requested
+                // one step ago), is copied into registers, and the next slice is requested into the same place at once.
                 const bf16_t *Hr = Hs + (h & 1) * 4096;                                                            // chunk h - 2
-                bf16x8 fh[2][2], f2[2][2];
+                bf16x8 fh[2][2], f2[4][2];
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) f2[kk][t] = *(const bf16x8 *)(w2_s + tile_off(t * 32 + lm, 2 * kk + lh));
                 auto load = [&](int kk, int s) {
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        fh[s][t] = *(const bf16x8 *)(Hr + tile_off(t * 32 + lm, 2 * kk + lh));
-                        f2[s][t] = *(const bf16x8 *)(s2 + tile_off(t * 32 + lm, 2 * kk + lh));
-                    }
+                    for (int t = 0; t < 2; ++t) fh[s][t] = *(const bf16x8 *)(Hr + tile_off(t * 32 + lm, 2 * kk + lh));
                 };
                 load(0, 0);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                if (h - 1 < nch) issue_w2(h - 1);
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
                     if (kk < 3) load(kk + 1, (kk + 1) & 1);
@@ -400,13 +421,14 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
                     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
                         for (int ct = 0; ct < 2; ++ct)
-                            y[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[kk & 1][ct], fh[kk & 1][rt], y[rt][ct], 0, 0, 0);
+                            y[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[kk][ct], fh[kk & 1][rt], y[rt][ct], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
+            LY_TSS(32 * (wave - 2) + 2 * h + 1);
         }
         LY_TS(8);
-        wait_item(NA + NQ - 1);                                                 // Be: every item of B is consumed
+        wait_item(NA + nch - 1);                                                // Be: every chunk and slice of B is consumed
         refill(HAS_QKV ? PC - 1 : 0, HAS_QKV ? PC + 1 : -1);                    // (the tile still needs stages 0-2)
         if (second) {
 #pragma unroll
@@ -436,7 +458,8 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             constexpr int par = decltype(PAR)::value ? 1 : 0;          // h & 1
             f32x16 &hout = hb[par], &hin = hb[par ^ 1];
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            const bf16_t *s1 = Ws + ((PB + (h < 2 ? h : 2 * h - 1)) % LY_NS) * IT_EL;               // W1(h)
+            LY_TSS(32 + 2 * h);
+            const bf16_t *s1 = Ws + ((SB0 + h) & 3) * IT_EL;                                        // W1(h)
             bf16_t *Hw = Hs + ((h - 1) & 1) * 4096;                                                  // chunk h - 1
             bf16x8 f1[2][KT];
             f32x4 b[4];
@@ -477,6 +500,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
+            LY_TSS(32 + 2 * h + 1);
         };
         first_step(T_{}, F_{}, F_{}, 0);
         for (int h = 1; h < nch; ++h) {
@@ -497,7 +521,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");             // Bz: LayerNorm1'(x'') is in As, the tile is dead
     LY_TS(10);
     f32x16 acc[LY_MAXCH + 1];                    // acc[c][e]: row wr*32 + lm, column c*64 + wc*32 + 8*(e/4) + 4*lh + e%4
-    const int i0q = NA + NQ;                     // first item of C
+    const int i0q = NA + nch;                    // first item of C
     if (loader) {
         for (int s = 0; 2 * s < nchq; ++s) {
             wait_item(i0q + min(2 * s + 1, nchq - 1));

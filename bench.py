@@ -24,7 +24,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the linear kernels on the default workload: FETCH_SIZE + WRITE_SIZE from two rocprofv3 --pmc
 # runs of this script, scaled by a copy kernel of known size (profiles/bench_cfg2_deit_tiny_hbm_traffic.md)
-LINEAR_HBM_BYTES_PER_LAUNCH = 45.3e6
+LINEAR_HBM_BYTES_PER_LAUNCH = 33.7e6
 
 
 def scores_for_sets(off, ids, n_groups=16, group_size=5):

@@ -12,15 +12,19 @@
 // Eight waves.  A wave that issues a load into the saturated L2 path is held at the issue stage, so the weight stream
 // has a wave of its own and the waves that compute issue no loads while they compute:
 //   waves 0-3 (2 x 2 over a 64 x 64 chunk): the MFMA work of A and C; in B the first product and the GELU;
-//   wave 4: the whole weight stream into a five-stage LDS ring (24 KB items);
-//   waves 5-7: in B the second product (wave 5 + j owns output columns 64 j .. 64 j + 63 of all 64 rows);
+//   wave 4: the weight stream into a ring of LDS stages (24 KB items; five stages in A and C, four in B);
+//   waves 5-7: in B the second product (wave 5 + j owns output columns 64 j .. 64 j + 63 of all 64 rows), each fed from its
+//             own tile of the current W2 slice in the fifth stage, which it refills itself as soon as it has copied the
+//             tile into registers.  A stage of a shared ring is freed by a workgroup barrier, so what is read in one step can
+//             be requested again in the next step at the earliest and the stream runs dry at every barrier; with W2 out
+//             of the ring the stream of W1 runs three chunks ahead and the loads of W2 never wait for a barrier;
 //   waves 4-7 together: At_k / Bt_k of the block's adapter into LDS, and the residual stream: they hold x' (fp32,
 //             4 threads per row) in registers from phase A to the end, do both LayerNorms on it and write x''.
 // The loop of B is bound by the number of instructions a wave issues (a wave issues one every five cycles or so,
 // whatever the instruction; two waves on a SIMD issue twice as many), which is why its two products sit on
 // different waves: the GELU's arithmetic and the second product's operand reads are issued side by side.
 // Phase boundaries pass a 64 x D fp32 tile through LDS; it takes the place of ring stages 0-2, so every phase's
-// stream starts in stage 3 and only two items of the next phase are prefetched across a boundary.
+// stream starts in stage 3 and at most two items of the next phase are prefetched across a boundary.
 #include "poly_dev.h"
 #include "rowtile.h"
 
@@ -441,13 +445,16 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
                         *(f32x4 *)(trow + (ct * 32 + 8 * g4) * 4) = f32x4{y[rt][ct][4 * g4], y[rt][ct][4 * g4 + 1], y[rt][ct][4 * g4 + 2], y[rt][ct][4 * g4 + 3]};
             }
         }
+        LY_TSS(200 + 10 * (wave - 4));
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // By: the y tile is complete
+        LY_TSS(201 + 10 * (wave - 4));
         float *dst = a.x_out + ((size_t)ob * a.T + t0 + (lt >> 2)) * D + 4 * (lt & 3);
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             xr[i] += *(const f32x4 *)(xtile + (lt >> 2) * XSTRIDE + (4 * i + (lt & 3)) * 16);
             if ((lt >> 2) < rows) *(f32x4 *)(dst + 16 * i) = xr[i];
         }
+        LY_TSS(202 + 10 * (wave - 4));
         if (HAS_QKV) ln_finish<KT, 4>(xr, gbq_s, a.eps, As, lt);
         LY_TS(9);
     } else {

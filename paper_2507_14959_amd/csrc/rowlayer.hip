@@ -54,7 +54,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     constexpr int A_EL = (KT < 2 ? 2 : KT) * 64 * 64;   // activation rows (KT tiles of [64][64]) / Bt_k / the two hidden tiles
     constexpr int IT_EL = KT * 64 * 64;          // one stream item: KT tiles of [64][64]
     constexpr int NLD = 8 * KT;                  // loads per item (all by wave 4): 64 rows of each tile, 8 rows per load
-    constexpr int NV = D / 16;                   // 16-byte pieces of an fp32 row per loader thread (4 threads per row)
+    constexpr int NV = D / 16;                   // 16-byte pieces of fp32 rows per loader thread (four rows, 16 threads per row)
     constexpr int XSTRIDE = D * 4 + 16;          // bytes per row of the fp32 hand-over tile
     extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
     bf16_t *As = lds, *Ws = lds + A_EL;
@@ -130,10 +130,18 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     f32x4 gb2v = {0.f, 0.f, 0.f, 0.f}, gbqv = {0.f, 0.f, 0.f, 0.f};
     float b1v[LY_MAX_DM / 256], bqv[(LY_MAX_NQ + 255) / 256], b2v = 0.f, bpv = 0.f;
     const bool res_early = !HAS_PROJ || a.res_block_of_out == nullptr;
+    // Rows of the residual stream in the loader waves: 16 threads per row.  Thread (slot = lt / 16, part = lt % 16) holds, of
+    // the four rows slot + 16 k, the 16-byte pieces part + 16 i (i < KT) as xr[k * KT + i]: the 16 lanes of a row read and
+    // write 256 contiguous bytes per instruction (whole cache lines), the row statistics are sums over a DPP row, and a
+    // thread needs the gains of only KT pieces for its four rows.
+    const int xslot = lt >> 4, xpart = lt & 15;
     auto load_res = [&](int rblk) {
-        const float *src = (HAS_PROJ ? a.res : a.x_out) + ((size_t)rblk * a.T + min(t0 + (lt >> 2), a.T - 1)) * D + 4 * (lt & 3);
 #pragma unroll
-        for (int i = 0; i < NV; ++i) xr[i] = *(const f32x4 *)(src + 16 * i);
+        for (int k = 0; k < 4; ++k) {
+            const float *src = (HAS_PROJ ? a.res : a.x_out) + ((size_t)rblk * a.T + min(t0 + xslot + 16 * k, a.T - 1)) * D + 4 * xpart;
+#pragma unroll
+            for (int i = 0; i < KT; ++i) xr[k * KT + i] = *(const f32x4 *)(src + 64 * i);
+        }
     };
     if (!loader) {
         if (HAS_PROJ) {
@@ -291,8 +299,50 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // loaders: x' (or x'') rows in xr -> LayerNorm -> As, gains from gb_s (the same 4-threads-per-row split as ln_finish)
     char *xtile = (char *)Ws;                    // the fp32 hand-over tile: ring stages 0-2
+    // loaders: xr += the tile (the product that the other waves staged)
+    auto add_tile = [&]() {
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int i = 0; i < KT; ++i) xr[k * KT + i] += *(const f32x4 *)(xtile + (xslot + 16 * k) * XSTRIDE + (xpart + 16 * i) * 16);
+    };
+    // loaders: the rows in xr -> LayerNorm (fp32 statistics, centred second moment) -> bf16 tiles at As, gains from gb_s
+    auto ln_rows = [&](const float *gb_s) {
+        f32x4 gn[KT], sh[KT];
+#pragma unroll
+        for (int i = 0; i < KT; ++i) { gn[i] = *(const f32x4 *)(gb_s + 4 * (xpart + 16 * i)); sh[i] = *(const f32x4 *)(gb_s + D + 4 * (xpart + 16 * i)); }
+        float mean[4], inv[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float t = 0.f;
+#pragma unroll
+            for (int i = 0; i < KT; ++i) t += xr[k * KT + i][0] + xr[k * KT + i][1] + xr[k * KT + i][2] + xr[k * KT + i][3];
+            mean[k] = row16_sum(t) * (1.0f / D);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float q = 0.f;
+#pragma unroll
+            for (int i = 0; i < KT; ++i)
+#pragma unroll
+                for (int z = 0; z < 4; ++z) { const float d = xr[k * KT + i][z] - mean[k]; q = fmaf(d, d, q); }
+            inv[k] = rsqrtf(row16_sum(q) * (1.0f / D) + a.eps);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float nmi = -mean[k] * inv[k];
+            const int row = xslot + 16 * k;
+#pragma unroll
+            for (int i = 0; i < KT; ++i) {
+                const int col = 4 * (xpart + 16 * i);         // first of this piece's 4 elements
+                bf16x4 o;
+#pragma unroll
+                for (int z = 0; z < 4; ++z) o[z] = (bf16_t)fmaf(fmaf(xr[k * KT + i][z], inv[k], nmi), gn[i][z], sh[i][z]);   // ((x - mean) inv) g + b
+                *(bf16x4 *)(As + (col >> 6) * 4096 + tile_off(row, (col & 63) >> 3) + (col & 4)) = o;
+            }
+        }
+    };
 
     // ================================================================ phase A: x' = res + o Wp + bp + lora
     if (HAS_PROJ) {
@@ -310,9 +360,8 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             LY_TS(5);
             asm volatile("s_barrier" ::: "memory");                             // Bs: the tile is complete
             LY_TS(6);
-#pragma unroll
-            for (int i = 0; i < NV; ++i) xr[i] += *(const f32x4 *)(xtile + (lt >> 2) * XSTRIDE + (4 * i + (lt & 3)) * 16);
-            ln_finish<KT, 4>(xr, gb2_s, a.eps, As, lt);
+            add_tile();
+            ln_rows(gb2_s);
             LY_TS(7);
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bl: LayerNorm2(x') is in As, the tile is dead
         } else {
@@ -346,7 +395,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         }
     } else {
         if (loader) {
-            ln_finish<KT, 4>(xr, gb2_s, a.eps, As, lt);
+            ln_rows(gb2_s);
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bl: LayerNorm2(x') is in As
         } else {
             asm volatile("s_barrier" ::: "memory");                             // Bl
@@ -448,14 +497,18 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         LY_TSS(200 + 10 * (wave - 4));
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // By: the y tile is complete
         LY_TSS(201 + 10 * (wave - 4));
-        float *dst = a.x_out + ((size_t)ob * a.T + t0 + (lt >> 2)) * D + 4 * (lt & 3);
+        add_tile();                                                             // x'' = x' + y
 #pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            xr[i] += *(const f32x4 *)(xtile + (lt >> 2) * XSTRIDE + (4 * i + (lt & 3)) * 16);
-            if ((lt >> 2) < rows) *(f32x4 *)(dst + 16 * i) = xr[i];
+        for (int k = 0; k < 4; ++k) {
+            const int row = xslot + 16 * k;
+            if (row < rows) {
+                float *dst = a.x_out + ((size_t)ob * a.T + t0 + row) * D + 4 * xpart;
+#pragma unroll
+                for (int i = 0; i < KT; ++i) *(f32x4 *)(dst + 64 * i) = xr[k * KT + i];
+            }
         }
         LY_TSS(202 + 10 * (wave - 4));
-        if (HAS_QKV) ln_finish<KT, 4>(xr, gbq_s, a.eps, As, lt);
+        if (HAS_QKV) ln_rows(gbq_s);
         LY_TS(9);
     } else {
         load_fa();

@@ -115,6 +115,15 @@ template <int TPR> __device__ __forceinline__ float row_group_sum(float s)
     if (TPR == 8) s += dpp_move<0x141>(s);       // row_half_mirror
     return s;
 }
+// sum over the 16 lanes of a DPP row, in every one of them
+__device__ __forceinline__ float row16_sum(float s)
+{
+    s += dpp_move<0xB1>(s);                      // quad_perm [1, 0, 3, 2]
+    s += dpp_move<0x4E>(s);                      // quad_perm [2, 3, 0, 1]
+    s += dpp_move<0x141>(s);                     // row_half_mirror: the other quad of eight lanes
+    s += dpp_move<0x140>(s);                     // row_mirror: the other eight lanes
+    return s;
+}
 template <int KT, int TPR>
 __device__ __forceinline__ void ln_finish(const f32x4 (&v)[64 * KT / TPR / 4], const float *gb_s, float eps, bf16_t *As, int tid)
 {

@@ -592,33 +592,43 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         asm volatile("s_barrier" ::: "memory");                                 // Bg2: expand done, Bt_k is dead
     } else {
         load_fa();
+        // the shrink first (At_k has been in LDS since phase B): these waves would only wait for the first chunks otherwise
+        bf16x8 fs = zero8;
+        if (lora_q) fs = shrink(a.r);
 #pragma unroll
         for (int s = 0; s < (LY_MAXCH + 1) / 2; ++s) {
             // uniform conditions, written as guards (not a break) so that the loop unrolls and acc stays in registers
             if (2 * s + 1 < nchq) linear_step(acc[2 * s], acc[2 * s + 1], 2 * s, PC + 2 * s, Nq, bq_s, std::true_type{});
             else if (2 * s < nchq) linear_step(acc[2 * s], acc[2 * s], 2 * s, PC + 2 * s, Nq, bq_s, std::false_type{});
         }
-        bf16x8 fs = zero8;
-        if (lora_q) fs = shrink(a.r);                                           // At_k landed before the first chunk did
         LY_TS(11);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // Bf2
         if (lora_q) {
+            // all operands first, then the MFMAs (one read-then-multiply per chunk would pay the LDS latency nine times)
+            bf16x8 fbt[LY_MAXCH];
+#pragma unroll
+            for (int c = 0; c < LY_MAXCH; ++c) fbt[c] = bt_frag(min(c * 64 + wc * 32 + lm, Nq - 1), a.r);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int c = 0; c < LY_MAXCH; ++c)
-                if (c < nchq) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bt_frag(min(c * 64 + wc * 32 + lm, Nq - 1), a.r), fs, acc[c], 0, 0, 0);
+                if (c < nchq) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fbt[c], fs, acc[c], 0, 0, 0);
         }
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // Bg2
         // A lane owns one row, so storing from registers would touch 32 cache lines per instruction with 8 bytes each:
         // the finished bf16 tile is laid out row-major in LDS and copied out in 16-byte pieces of consecutive threads
         const int qstride = ((Nq * 2 + 255) & ~255) + 16;
-        char *trow = (char *)lds + (wr * 32 + lm) * qstride + (wc * 32 + 4 * lh) * 2;
+        // A lane holds columns 8 g + 4 lh + {0..3} of its row; the two lanes of a row trade halves (lane < 32 gives its piece of
+        // group g + 1 for the other's piece of group g) so that each ends up with eight consecutive columns: half as many
+        // LDS writes, 16 bytes each (a wave's LDS writes cost the same whatever their width).  Nq is a multiple of 64.
+        char *trow = (char *)lds + (wr * 32 + lm) * qstride + (wc * 32 + 8 * lh) * 2;
 #pragma unroll
         for (int c = 0; c < LY_MAXCH; ++c) {
             if (c < nchq) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const bf16x4 w = {(bf16_t)acc[c][4 * g], (bf16_t)acc[c][4 * g + 1], (bf16_t)acc[c][4 * g + 2], (bf16_t)acc[c][4 * g + 3]};
-                    if ((c + 1) * 64 <= Nq || c * 64 + wc * 32 + 8 * g + 4 * lh < Nq) *(bf16x4 *)(trow + (c * 64 + 8 * g) * 2) = w;
+                for (int g = 0; g < 4; g += 2) {
+                    const bf16x4 w0 = {(bf16_t)acc[c][4 * g], (bf16_t)acc[c][4 * g + 1], (bf16_t)acc[c][4 * g + 2], (bf16_t)acc[c][4 * g + 3]};
+                    const bf16x4 w1 = {(bf16_t)acc[c][4 * g + 4], (bf16_t)acc[c][4 * g + 5], (bf16_t)acc[c][4 * g + 6], (bf16_t)acc[c][4 * g + 7]};
+                    *(u32x4 *)(trow + (c * 64 + 8 * g) * 2) = pair_halves(w0, w1);
                 }
             }
         }

@@ -100,6 +100,20 @@ template <int KT> __device__ __forceinline__ void ln_gb_store(f32x4 v, float *gb
 {
     if (tid < 32 * KT) *(f32x4 *)(gb_s + 4 * tid) = v;
 }
+// Lanes l and l + 32 each hold two 8-byte pieces p0, p1.  Returns, in lane l < 32, (own p0, the other lane's p0) and, in lane
+// l + 32, (the other lane's p1, own p1): with p = four consecutive bf16 columns at offset 4 * (lane / 32) of an 8-column
+// group, lane l gets all eight columns of the first group and lane l + 32 all eight of the second.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x4 pair_halves(bf16x4 p0, bf16x4 p1)
+{
+    const u32x2 a = __builtin_bit_cast(u32x2, p0), b = __builtin_bit_cast(u32x2, p1);
+    // v_permlane32_swap: lanes 32-63 of the first operand trade places with lanes 0-31 of the second
+    const auto r0 = __builtin_amdgcn_permlane32_swap(a[0], b[0], false, false);
+    const auto r1 = __builtin_amdgcn_permlane32_swap(a[1], b[1], false, false);
+    return u32x4{r0[0], r1[0], r0[1], r1[1]};
+}
+
 // sum over the TPR (4 or 8) adjacent lanes that share a row, in every one of them: data-parallel-primitive moves inside
 // the quad (lane ^ 1, lane ^ 2) and across the two quads of eight lanes (mirror: every lane of a quad holds the quad's sum by
 // then) -- a shuffle through the LDS crossbar costs a hundred-odd cycles per step

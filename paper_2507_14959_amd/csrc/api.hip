@@ -119,11 +119,11 @@ extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *b
     const size_t es = elt_size(dt);
     const int *R_dev = &w.meta->R;
 
-    POLY_TRY(launch_prep(row_offsets, adapter_ids, F, R, m->n_adapters, w.meta, w.frame_of_row, w.adapter_of_row, dev_status, st));
-
-    // tokens: x[f][0] = cls + pos[0]; x[f][1 + t] = patch_t W_pe + b_pe + pos[1 + t]
+    // tokens: x[f][0] = cls + pos[0]; x[f][1 + t] = patch_t W_pe + b_pe + pos[1 + t].  The same launch checks the CSR arrays and
+    // builds the row maps (nothing before the first adapted layer needs them).
     POLY_TRY(launch_im2col(frames, w.patches, F, m->H, m->W, m->patch, dt, w.xa, base->cls, base->pos, T, D, out_merged,
-                           out_merged ? (size_t)F * K : 0, st));
+                           out_merged ? (size_t)F * K : 0, row_offsets, adapter_ids, R, m->n_adapters, w.meta, w.frame_of_row,
+                           w.adapter_of_row, dev_status, st));
     {
         GemmArgs g = {};
         g.A = w.patches; g.Wt = base->patch_w; g.bias = base->patch_b;

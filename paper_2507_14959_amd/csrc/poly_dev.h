@@ -254,9 +254,11 @@ int launch_attention(const void *qkv, void *out, int T, int D, int heads, int n_
 // ---- bookkeeping and row-wise stages (rowops.hip) ----
 int launch_prep(const int32_t *row_offsets, const int32_t *adapter_ids, int F, int R_cap, int n_adapters, PolyMeta *meta,
                 int32_t *frame_of_row, int32_t *adapter_of_row, int32_t *dev_status, hipStream_t st);
-// patches <- frames (im2col), x[f][0][:] <- cls + pos[0], merged[0 .. n_merged) <- 0
+// patches <- frames (im2col), x[f][0][:] <- cls + pos[0], merged[0 .. n_merged) <- 0; and, when row_offsets is given, the work of
+// launch_prep as one more block of the same launch
 int launch_im2col(const void *frames, void *patches, int F, int H, int W, int p, int dtype, float *x, const float *cls, const float *pos,
-                  int T_tok, int D, float *merged, size_t n_merged, hipStream_t st);
+                  int T_tok, int D, float *merged, size_t n_merged, const int32_t *row_offsets, const int32_t *adapter_ids, int R_cap,
+                  int n_adapters, PolyMeta *meta, int32_t *frame_of_row, int32_t *adapter_of_row, int32_t *dev_status, hipStream_t st);
 int launch_head(const float *x, const int *src_block_of_row, int T, int D, const float *gain, const float *shift, float eps,
                 const void *head_w, const float *head_b, int C, const int *adapter_of_row, const int *frame_of_row,
                 const int32_t *class_map, int K, const PolyMeta *meta, int R_cap, float *logits, float *scores, float *merged, int dtype,

@@ -7,8 +7,8 @@ namespace {
 // ------------------------------------------------------------------ CSR check + row maps
 // One block.  Validates row_offsets / adapter_ids against (F, R_cap, n_adapters) and builds
 // frame_of_row / adapter_of_row.  On any violation nothing downstream runs (meta->R = 0).
-__global__ void prep_kernel(const int32_t *row_offsets, const int32_t *adapter_ids, int F, int R_cap, int n_adapters,
-                            PolyMeta *meta, int32_t *frame_of_row, int32_t *adapter_of_row, int32_t *dev_status)
+__device__ __forceinline__ void prep_block(const int32_t *row_offsets, const int32_t *adapter_ids, int F, int R_cap, int n_adapters,
+                                           PolyMeta *meta, int32_t *frame_of_row, int32_t *adapter_of_row, int32_t *dev_status)
 {
     __shared__ int bad;
     if (threadIdx.x == 0) bad = 0;
@@ -36,6 +36,17 @@ __global__ void prep_kernel(const int32_t *row_offsets, const int32_t *adapter_i
         if (dev_status) *dev_status = meta->status;
     }
 }
+__global__ void prep_kernel(const int32_t *row_offsets, const int32_t *adapter_ids, int F, int R_cap, int n_adapters,
+                            PolyMeta *meta, int32_t *frame_of_row, int32_t *adapter_of_row, int32_t *dev_status)
+{
+    prep_block(row_offsets, adapter_ids, F, R_cap, n_adapters, meta, frame_of_row, adapter_of_row, dev_status);
+}
+struct PrepArgs {       // the CSR check as the last block of another launch (row_offsets == nullptr: none)
+    const int32_t *row_offsets, *adapter_ids;
+    int F, R_cap, n_adapters;
+    PolyMeta *meta;
+    int32_t *frame_of_row, *adapter_of_row, *dev_status;
+};
 
 // ------------------------------------------------------------------ patch gathering
 // patches[(f*P + ty*gw + tx)][(i*p + j)*3 + c] = frame[f][ty*p + i][tx*p + j][c]; a run of 3p values
@@ -44,11 +55,16 @@ __global__ void prep_kernel(const int32_t *row_offsets, const int32_t *adapter_i
 // rows x[f][0][:] = cls + pos[0] and clears the merged-score buffer (both are needed much later: two launches less).
 template <typename T, int VEC>
 __global__ void im2col_kernel(const T *frames, T *patches, int F, int H, int W, int p, float *x, const float *cls, const float *pos,
-                              int T_tok, int D, float *merged, size_t n_merged)
+                              int T_tok, int D, float *merged, size_t n_merged, const PrepArgs pa)
 {
+    const int nblk = pa.row_offsets ? gridDim.x - 1 : gridDim.x;   // the last block checks the CSR arrays (one launch less)
+    if ((int)blockIdx.x == nblk) {
+        prep_block(pa.row_offsets, pa.adapter_ids, pa.F, pa.R_cap, pa.n_adapters, pa.meta, pa.frame_of_row, pa.adapter_of_row, pa.dev_status);
+        return;
+    }
     const int gw = W / p, gh = H / p, run = 3 * p / VEC;         // vectors per contiguous run
     const size_t total = (size_t)F * gh * gw * p * run;
-    const size_t gtid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, gsz = (size_t)gridDim.x * blockDim.x;
+    const size_t gtid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, gsz = (size_t)nblk * blockDim.x;
     typedef T vec_t __attribute__((ext_vector_type(VEC)));
     for (size_t idx = gtid; idx < total; idx += gsz) {
         size_t q = idx;
@@ -245,21 +261,26 @@ int launch_prep(const int32_t *row_offsets, const int32_t *adapter_ids, int F, i
 }
 
 int launch_im2col(const void *frames, void *patches, int F, int H, int W, int p, int dtype, float *x, const float *cls, const float *pos,
-                  int T_tok, int D, float *merged, size_t n_merged, hipStream_t st)
+                  int T_tok, int D, float *merged, size_t n_merged, const int32_t *row_offsets, const int32_t *adapter_ids, int R_cap,
+                  int n_adapters, PolyMeta *meta, int32_t *frame_of_row, int32_t *adapter_of_row, int32_t *dev_status, hipStream_t st)
 {
+    const PrepArgs pa = {row_offsets, adapter_ids, F, R_cap, n_adapters, meta, frame_of_row, adapter_of_row, dev_status};
     const size_t total = (size_t)F * H * W * 3;
-    if (total == 0 && n_merged == 0) return POLY_OK;
+    if (total == 0 && n_merged == 0) {
+        if (row_offsets) return launch_prep(row_offsets, adapter_ids, F, R_cap, n_adapters, meta, frame_of_row, adapter_of_row, dev_status, st);
+        return POLY_OK;
+    }
     // 16-byte vectors when a run of 3p elements is a whole number of them and rows of the frame keep them aligned
     const int vec = dtype == POLY_BF16 ? 8 : 4;
     const bool wide = (3 * p) % vec == 0 && (3 * W) % vec == 0 && ((uintptr_t)frames & 15) == 0 && ((uintptr_t)patches & 15) == 0;
     const size_t work = (wide ? total / vec : total) > n_merged ? (wide ? total / vec : total) : n_merged;
-    const unsigned blocks = (unsigned)((work + 255) / 256 > 65536 ? 65536 : (work + 255) / 256 < 1 ? 1 : (work + 255) / 256);
+    const unsigned blocks = (unsigned)((work + 255) / 256 > 65536 ? 65536 : (work + 255) / 256 < 1 ? 1 : (work + 255) / 256) + (row_offsets ? 1 : 0);
     if (dtype == POLY_BF16) {
-        if (wide) POLY_LAUNCH(POLY_STAGE_OTHER, (im2col_kernel<bf16_t, 8>), dim3(blocks), dim3(256), st, (const bf16_t *)frames, (bf16_t *)patches, F, H, W, p, x, cls, pos, T_tok, D, merged, n_merged);
-        else POLY_LAUNCH(POLY_STAGE_OTHER, (im2col_kernel<bf16_t, 1>), dim3(blocks), dim3(256), st, (const bf16_t *)frames, (bf16_t *)patches, F, H, W, p, x, cls, pos, T_tok, D, merged, n_merged);
+        if (wide) POLY_LAUNCH(POLY_STAGE_OTHER, (im2col_kernel<bf16_t, 8>), dim3(blocks), dim3(256), st, (const bf16_t *)frames, (bf16_t *)patches, F, H, W, p, x, cls, pos, T_tok, D, merged, n_merged, pa);
+        else POLY_LAUNCH(POLY_STAGE_OTHER, (im2col_kernel<bf16_t, 1>), dim3(blocks), dim3(256), st, (const bf16_t *)frames, (bf16_t *)patches, F, H, W, p, x, cls, pos, T_tok, D, merged, n_merged, pa);
     } else {
-        if (wide) POLY_LAUNCH(POLY_STAGE_OTHER, (im2col_kernel<float, 4>), dim3(blocks), dim3(256), st, (const float *)frames, (float *)patches, F, H, W, p, x, cls, pos, T_tok, D, merged, n_merged);
-        else POLY_LAUNCH(POLY_STAGE_OTHER, (im2col_kernel<float, 1>), dim3(blocks), dim3(256), st, (const float *)frames, (float *)patches, F, H, W, p, x, cls, pos, T_tok, D, merged, n_merged);
+        if (wide) POLY_LAUNCH(POLY_STAGE_OTHER, (im2col_kernel<float, 4>), dim3(blocks), dim3(256), st, (const float *)frames, (float *)patches, F, H, W, p, x, cls, pos, T_tok, D, merged, n_merged, pa);
+        else POLY_LAUNCH(POLY_STAGE_OTHER, (im2col_kernel<float, 1>), dim3(blocks), dim3(256), st, (const float *)frames, (float *)patches, F, H, W, p, x, cls, pos, T_tok, D, merged, n_merged, pa);
     }
     return hip_ok();
 }

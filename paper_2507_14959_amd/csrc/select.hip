@@ -9,6 +9,8 @@
 // sequential pass that only runs when a state is carried or context_copy is set.
 #include "poly_dev.h"
 
+#include <type_traits>
+
 namespace {
 
 constexpr int CH = 128;  // frames per pass
@@ -30,13 +32,13 @@ __global__ __launch_bounds__(256) void select_kernel(const float *scores, int F,
     __shared__ uint64_t cmask[MMAX][KWMAX];    // labels that the context at a scan position provides
     __shared__ uint64_t mem_id[MMAX][KWMAX], prov_id[MMAX][KWMAX];   // member / provided labels by context id
     __shared__ uint64_t Y[CH][KWMAX];          // Y_t
-    __shared__ uint64_t U[CH][KWMAX];          // still uncovered while scanning
     __shared__ uint64_t S[CH];                 // S_t as a mask over scan positions
     __shared__ int cnt[CH];
     __shared__ int unc[CH];
     __shared__ uint64_t prevY[KWMAX], prevProv[KWMAX];
     __shared__ uint64_t prevS;
     __shared__ int prevValid, total, total_unc;
+    __shared__ int wtot[4], wunc[4];           // per wave: selected contexts, uncovered labels (scan below)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int KW = (K + 63) / 64;
@@ -115,26 +117,47 @@ __global__ __launch_bounds__(256) void select_kernel(const float *scores, int F,
                 const int w = w0 + u;
                 if (w < n * KW) {     // uniform
                     const uint64_t m = __ballot((w % KW) * 64 + lane < K && sv[u] >= theta);
-                    if (lane == 0) { Y[w / KW][w % KW] = m; U[w / KW][w % KW] = m; }
+                    if (lane == 0) Y[w / KW][w % KW] = m;
                 }
             }
         }
         __syncthreads();
-        // greedy cover, one frame per thread
+        // greedy cover, one frame per thread; the uncovered set stays in registers (a round trip through LDS per scan position
+        // and word made this the longest phase of the kernel)
         if (tid < n) {
-            uint64_t sel = 0;
-            bool left = false;
-            for (int j = 0; j < KW; ++j) left |= U[tid][j] != 0;
-            for (int pos = 0; pos < M && left; ++pos) {
-                bool got = false;
-                for (int j = 0; j < KW; ++j) got |= (U[tid][j] & cmask[pos][j]) != 0;
-                if (got) {
-                    sel |= 1ull << pos;
-                    left = false;
-                    for (int j = 0; j < KW; ++j) { U[tid][j] &= ~cmask[pos][j]; left |= U[tid][j] != 0; }
+            // NW: compile-time bound of the words per label set (the registers are indexed by unrolled loops)
+            auto greedy = [&](auto NWC) {
+                constexpr int NW = decltype(NWC)::value;
+                uint64_t u[NW];
+                bool left = false;
+#pragma unroll
+                for (int j = 0; j < NW; ++j) {
+                    u[j] = j < KW ? Y[tid][j] : 0ull;
+                    left |= u[j] != 0;
                 }
-            }
-            S[tid] = sel;
+                uint64_t sel = 0;
+                for (int pos = 0; pos < M && left; ++pos) {
+                    bool got = false;
+#pragma unroll
+                    for (int j = 0; j < NW; ++j)
+                        if (NW <= 2 || j < KW) got |= (u[j] & cmask[pos][j]) != 0;
+                    if (got) {
+                        sel |= 1ull << pos;
+                        left = false;
+#pragma unroll
+                        for (int j = 0; j < NW; ++j)
+                            if (NW <= 2 || j < KW) { u[j] &= ~cmask[pos][j]; left |= u[j] != 0; }
+                    }
+                }
+                S[tid] = sel;
+                int nu = 0;
+#pragma unroll
+                for (int j = 0; j < NW; ++j) nu += __popcll(u[j]);
+                unc[tid] = nu;                   // uncovered labels of the greedy result (recomputed below if a set is reused)
+            };
+            if (KW <= 2) greedy(std::integral_constant<int, 2>{});       // (cmask words past KW are never read as set: u is 0 there)
+            else if (KW <= 4) greedy(std::integral_constant<int, 4>{});
+            else greedy(std::integral_constant<int, KWMAX>{});
         }
         __syncthreads();
         // reuse branches of Alg. 2, in frame order
@@ -161,30 +184,47 @@ __global__ __launch_bounds__(256) void select_kernel(const float *scores, int F,
             }
         }
         __syncthreads();
-        // sizes, uncovered labels
+        // sizes; uncovered labels again where the reuse branches may have replaced the set
         if (tid < n) {
             const uint64_t sel = S[tid];
-            int u = 0;
-            for (int j = 0; j < KW; ++j) {
-                uint64_t pv = 0;
-                for (int pos = 0; pos < M; ++pos)
-                    if ((sel >> pos) & 1ull) pv |= cmask[pos][j];
-                u += __popcll(Y[tid][j] & ~pv);
+            if (sequential) {
+                int u = 0;
+                for (int j = 0; j < KW; ++j) {
+                    uint64_t pv = 0;
+                    for (int pos = 0; pos < M; ++pos)
+                        if ((sel >> pos) & 1ull) pv |= cmask[pos][j];
+                    u += __popcll(Y[tid][j] & ~pv);
+                }
+                unc[tid] = u;
             }
             cnt[tid] = __popcll(sel);
-            unc[tid] = u;
         }
         __syncthreads();
-        if (tid == 0) {  // exclusive scan of at most CH small counts
-            int run = total, ru = total_unc;
-            for (int t = 0; t < n; ++t) {
-                const int c = cnt[t];
-                cnt[t] = run;
-                run += c;
-                ru += unc[t];
-                row_offsets[f0 + t + 1] = run;
+        // exclusive scan of at most CH counts: inside each wave by shuffles, then the totals of the waves before
+        {
+            const int c = tid < n ? cnt[tid] : 0, uu = tid < n ? unc[tid] : 0;
+            int inc = c, usum = uu;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int v = __shfl_up(inc, o, 64);
+                if (lane >= o) inc += v;
             }
-            total = run; total_unc = ru;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) usum += __shfl_xor(usum, o, 64);
+            if (lane == 63) { wtot[wave] = inc; wunc[wave] = usum; }
+            __syncthreads();
+            int before = total, ubefore = total_unc;
+            for (int w = 0; w < wave; ++w) before += wtot[w];
+            if (tid < n) {
+                cnt[tid] = before + inc - c;
+                row_offsets[f0 + tid + 1] = before + inc;
+            }
+            __syncthreads();
+            if (tid == 0) {
+                int run = total;
+                for (int w = 0; w < 4; ++w) { run += wtot[w]; ubefore += wunc[w]; }
+                total = run; total_unc = ubefore;
+            }
         }
         __syncthreads();
         if (tid < n) {

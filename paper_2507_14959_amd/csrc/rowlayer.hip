@@ -19,7 +19,7 @@
 //             be requested again in the next step at the earliest and the stream runs dry at every barrier; with W2 out
 //             of the ring the stream of W1 runs three chunks ahead and the loads of W2 never wait for a barrier;
 //   waves 4-7 together: At_k / Bt_k of the block's adapter into LDS, and the residual stream: they hold x' (fp32,
-//             4 threads per row) in registers from phase A to the end, do both LayerNorms on it and write x''.
+//             16 threads per row) in registers from phase A to the end, do both LayerNorms on it and write x''.
 // The loop of B is bound by the number of instructions a wave issues (a wave issues one every five cycles or so,
 // whatever the instruction; two waves on a SIMD issue twice as many), which is why its two products sit on
 // different waves: the GELU's arithmetic and the second product's operand reads are issued side by side.

@@ -60,6 +60,19 @@ def test_row_kernels_all_widths(D, heads, Dm, hw, r, targets, L0):
     compare(cfg, w, frames, off, ids, L0, K=cfg.n_adapters * cfg.C)
 
 
+@pytest.mark.parametrize("D,heads,Dm,hw,r,targets,L0", [(64, 1, 192, 64, 16, 1, 1), (128, 2, 384, 64, 8, 3, 0), (192, 3, 768, 40, 8, 3, 2)])
+def test_row_kernels_repeat_bitwise(D, heads, Dm, hw, r, targets, L0):
+    """The fused row kernels hand LDS stages from a stream wave to the computing waves by hand-counted waits: a stage that is
+    refilled one step early shows up as run-to-run differences long before it shows up as a wrong answer."""
+    cfg, w, frames, off, ids = synth.make_small_case(60 + D + r, dtype=synth.DT_BF16, targets=targets, L=4, F=4, r=r, max_set=3,
+                                                      n_adapters=5, D=D, heads=heads, Dm=Dm, hw=hw, patch=8)
+    model = binding.DeviceModel(cfg, w, L0=L0)
+    first = binding.run_forward(model, frames, off, ids)["logits"]
+    for _ in range(8):
+        again = binding.run_forward(model, frames, off, ids)["logits"]
+        assert np.array_equal(first, again)
+
+
 def test_frames_without_adapters_and_empty_batch():
     cfg, w, frames, _, _ = synth.make_small_case(50, dtype=synth.DT_BF16, F=4)
     off, ids = synth.sets_to_csr([[], [1, 0], [], [2]])

@@ -482,7 +482,9 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         }
         LY_TS(8);
         wait_item(NA + nch - 1);                                                // Be: every chunk and slice of B is consumed
+        LY_TSS(203 + 10 * (wave - 4));
         refill(HAS_QKV ? PC - 1 : 0, HAS_QKV ? PC + 1 : -1);                    // (the tile still needs stages 0-2)
+        LY_TSS(204 + 10 * (wave - 4));
         if (second) {
 #pragma unroll
             for (int rt = 0; rt < 2; ++rt) {

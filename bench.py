@@ -221,6 +221,49 @@ def main():
             "shrink_us": round(s5 * 1e6, 1),
             "shrink_GBs": round(2 * (R5 * 197 * 768 + R5 * 197 * 16) / s5 / 1e9, 1),
             "shrink_gflops": round(sh5 / s5 / 1e9, 1)}
+        del X, Wt, At, Bt, Y, ws5
+        # config 4: a 1024-frame label stream in 16 batches of 64 frames, poly_select + poly_forward per batch on the DeiT-tiny
+        # model (every batch reuses the same 64 synthetic frames: the cost of a batch depends on its adapter sets, not its pixels)
+        scores4_np, _ = synth.make_label_stream(1024)
+        model4 = binding.DeviceModel(cfg, w, L0=0)
+        frames4 = model4.frames_to_device(synth.make_frames(cfg, 64, np.random.default_rng(synth.seed_of(4))))
+        scores4 = torch.from_numpy(scores4_np).to(dev)
+        mem4 = torch.from_numpy(mem_np).to(dev)
+        cap4 = 3 * 64
+        off4 = torch.zeros(65, dtype=torch.int32, device=dev)
+        ids4 = torch.zeros(cap4, dtype=torch.int32, device=dev)
+        cnt4 = torch.zeros(2, dtype=torch.int32, device=dev)
+        out4 = torch.zeros(cap4, cfg.C, device=dev)
+        merged4 = torch.zeros(64, K_labels, device=dev)
+        ws4 = torch.empty(binding.poly_forward_workspace_bytes(model4, 64, cap4), dtype=torch.uint8, device=dev)
+
+        def stream_pass():
+            for a0 in range(0, 1024, 64):
+                binding.poly_select(scores4[a0:a0 + 64], mem4, off4, ids4, cnt4)
+                binding.poly_forward(model4, frames4, off4, ids4, cap4, out4, ws4, out_merged=merged4)
+        sec4 = timed(stream_pass, 5, 2)
+        binding.poly_select(scores4[960:1024], mem4, off4, ids4, cnt4)
+        torch.cuda.synchronize()
+        extra["stream_cfg4"] = {"frames_per_s": round(1024 / sec4, 1), "ms_per_64_frame_batch": round(sec4 / 16 * 1e3, 3),
+                                "row_blocks_last_batch": int(cnt4.cpu().numpy()[0])}
+        del model4, frames4, ws4
+        # config 3: ViT-base, 64 frames, adapters on qkv, proj, fc1 and fc2 (forward alone; its adapter sets are given)
+        cfg3, w3, frames3_np, off3_np, ids3_np = synth.make_forward_case(3)
+        model3 = binding.DeviceModel(cfg3, w3, L0=0)
+        del w3
+        frames3 = model3.frames_to_device(frames3_np)
+        F3, R3 = frames3_np.shape[0], int(off3_np[-1])
+        off3 = torch.from_numpy(off3_np.astype(np.int32)).to(dev)
+        ids3 = torch.from_numpy(ids3_np.astype(np.int32)).to(dev)
+        out3 = torch.zeros(R3, cfg3.C, device=dev)
+        ws3 = torch.empty(binding.poly_forward_workspace_bytes(model3, F3, R3), dtype=torch.uint8, device=dev)
+        sec3 = timed(lambda: binding.poly_forward(model3, frames3, off3, ids3, R3, out3, ws3), 10, 3)
+        T3 = 1 + (cfg3.H // cfg3.patch) * (cfg3.W // cfg3.patch)
+        fl3 = R3 * cfg3.L * (2.0 * T3 * (4 * cfg3.D ** 2 + 2 * cfg3.D * cfg3.Dm) + 4.0 * T3 * T3 * cfg3.D
+                             + 2.0 * T3 * cfg3.r * (4 * cfg3.D + 2 * cfg3.D + 2 * (cfg3.D + cfg3.Dm))) + F3 * 2.0 * (T3 - 1) * 768 * cfg3.D
+        extra["vit_base_cfg3"] = {"frames_per_s": round(F3 / sec3, 1), "ms_per_call": round(sec3 * 1e3, 2), "row_blocks": R3,
+                                  "algorithmic_tflops": round(fl3 / sec3 / 1e12, 1), "frac_mfma": round(fl3 / sec3 / 1e12 / PEAK_BF16_TFLOPS, 4)}
+        del model3, frames3, ws3
         result["extra"] = extra
 
     if not args.no_cpu:

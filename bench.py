@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--L0", type=int, default=0, help="first adapted layer (0 = all layers adapted; 10 = last 20 %%)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-checker baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements (L0=10, isolated linear)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also print a second JSON line: frames/s for 1..5 adapters per frame, all layers adapted vs the last 20 %% only")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 256 MiB device copy (a kernel of known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -107,12 +109,12 @@ def main():
     scores_np = scores_for_sets(off_np, ids_np)
     K_labels = mem_np.shape[1]
 
-    def make_step(L0):
+    def make_step(L0, scores_np=scores_np, per_frame=3):
         model = binding.DeviceModel(cfg, w, L0=L0)
         frames = model.frames_to_device(frames_np)
         scores = torch.from_numpy(scores_np).to(dev)
         mem = torch.from_numpy(mem_np).to(dev)
-        cap = 3 * F
+        cap = per_frame * F
         off = torch.zeros(F + 1, dtype=torch.int32, device=dev)
         ids = torch.zeros(cap, dtype=torch.int32, device=dev)
         cnt = torch.zeros(2, dtype=torch.int32, device=dev)
@@ -280,6 +282,25 @@ def main():
         result["max_abs_score_error_vs_oracle"] = err
 
     print(json.dumps(result))
+
+    if args.sweep:
+        # adapters per frame x placement (the synthetic analogue of the paper's Figs. 3-4): every frame gets exactly n adapters,
+        # ids uniform without replacement; the step is the same select + forward + merge as above
+        rng = np.random.default_rng(synth.seed_of(2) + 77)
+        table = {}
+        for n_ad in range(1, 6):
+            ids_s = np.concatenate([np.sort(rng.choice(cfg.n_adapters, size=n_ad, replace=False)) for _ in range(F)]).astype(np.int32)
+            off_s = (np.arange(F + 1) * n_ad).astype(np.int32)
+            sc_s = scores_for_sets(off_s, ids_s)
+            row = {}
+            for L0s in (0, cfg.polymorph_L0()):
+                step_s, keep_s = make_step(L0s, sc_s, 5)
+                sec_s = timed(step_s, 50, 10)
+                assert np.array_equal(keep_s[4].cpu().numpy(), off_s) and np.array_equal(keep_s[5].cpu().numpy()[:len(ids_s)], ids_s)
+                row[f"L0={L0s}"] = round(F / sec_s, 1)
+                del step_s, keep_s
+            table[str(n_ad)] = row
+        print(json.dumps({"sweep": "frames/s, config-2 model, 32 frames, n adapters on every frame", "adapters_per_frame": table}))
 
 
 if __name__ == "__main__":

@@ -105,6 +105,44 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float *x, T *y, co
     for (int k = lane; k < D; k += 64) yr[k] = from_f32<T>((xr[k] - mean) * inv * gain[k] + shift[k]);
 }
 
+// D = 256 NV: the row stays in registers (NV 16-byte pieces per lane), read once and written in 8- or 16-byte pieces
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *x, T *y, const float *gain, const float *shift, float eps,
+                                                            int rows_per_block, int n_blocks, const int *n_blocks_dev)
+{
+    constexpr int D = 256 * NV;
+    const int lane = threadIdx.x & 63;
+    const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const size_t rows_cap = (size_t)n_blocks * rows_per_block;
+    const float *xr = x + (row < rows_cap ? row : rows_cap - 1) * D + 4 * lane;     // requested before the row count is known
+    f32x4 v[NV], g[NV], b[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i] = *(const f32x4 *)(xr + 256 * i);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) { g[i] = *(const f32x4 *)(gain + 4 * lane + 256 * i); b[i] = *(const f32x4 *)(shift + 4 * lane + 256 * i); }
+    const int nb = n_blocks_dev ? min(*n_blocks_dev, n_blocks) : n_blocks;
+    if (row >= (size_t)nb * rows_per_block) return;
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
+    const float mean = wave_sum(s) / D;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int z = 0; z < 4; ++z) { const float d = v[i][z] - mean; q += d * d; }
+    const float inv = rsqrtf(wave_sum(q) / D + eps);
+    T *yr = y + row * D + 4 * lane;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        typedef T out4 __attribute__((ext_vector_type(4)));
+        out4 o;
+#pragma unroll
+        for (int z = 0; z < 4; ++z) o[z] = from_f32<T>((v[i][z] - mean) * inv * g[i][z] + b[i][z]);
+        *(out4 *)(yr + 256 * i) = o;
+    }
+}
+
 // ------------------------------------------------------------------ LoRA shrink
 // bf16: one wave per 32 rows of one output block; S = scale * X At_k^T on the MFMA, operands read straight
 // from global memory (each lane 16 contiguous bytes along K), result zero padded to RP columns.
@@ -291,7 +329,16 @@ int launch_layernorm(const float *x, void *y, const float *gain, const float *sh
     const size_t rows = (size_t)n_blocks * T;
     if (rows == 0) return POLY_OK;
     const unsigned blocks = (unsigned)((rows + 3) / 4);
-    if (dtype == POLY_BF16)
+    const bool aligned = ((uintptr_t)x & 15) == 0 && ((uintptr_t)y & 15) == 0 && ((uintptr_t)gain & 15) == 0 && ((uintptr_t)shift & 15) == 0;
+    if (dtype == POLY_BF16 && aligned && D == 768) {
+        POLY_LAUNCH(POLY_STAGE_NORM, (layernorm_vec_kernel<bf16_t, 3>), dim3(blocks), dim3(256), st, x, (bf16_t *)y, gain, shift, eps, T, n_blocks, n_blocks_dev);
+    } else if (dtype == POLY_BF16 && aligned && D == 1024) {
+        POLY_LAUNCH(POLY_STAGE_NORM, (layernorm_vec_kernel<bf16_t, 4>), dim3(blocks), dim3(256), st, x, (bf16_t *)y, gain, shift, eps, T, n_blocks, n_blocks_dev);
+    } else if (dtype == POLY_BF16 && aligned && D == 512) {
+        POLY_LAUNCH(POLY_STAGE_NORM, (layernorm_vec_kernel<bf16_t, 2>), dim3(blocks), dim3(256), st, x, (bf16_t *)y, gain, shift, eps, T, n_blocks, n_blocks_dev);
+    } else if (dtype == POLY_BF16 && aligned && D == 256) {
+        POLY_LAUNCH(POLY_STAGE_NORM, (layernorm_vec_kernel<bf16_t, 1>), dim3(blocks), dim3(256), st, x, (bf16_t *)y, gain, shift, eps, T, n_blocks, n_blocks_dev);
+    } else if (dtype == POLY_BF16)
         POLY_LAUNCH(POLY_STAGE_NORM, layernorm_kernel<bf16_t>, dim3(blocks), dim3(256), st, x, (bf16_t *)y, gain, shift, D, eps, T, n_blocks, n_blocks_dev);
     else
         POLY_LAUNCH(POLY_STAGE_NORM, layernorm_kernel<float>, dim3(blocks), dim3(256), st, x, (float *)y, gain, shift, D, eps, T, n_blocks, n_blocks_dev);

@@ -144,42 +144,65 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *x, T *y
 }
 
 // ------------------------------------------------------------------ LoRA shrink
-// bf16: one wave per 32 rows of one output block; S = scale * X At_k^T on the MFMA, operands read straight
-// from global memory (each lane 16 contiguous bytes along K), result zero padded to RP columns.
+// bf16: one workgroup per 32 rows of one output block; S = scale * X At_k^T on the MFMA, operands read straight
+// from global memory (each lane 16 contiguous bytes along K). The four waves take a quarter of K each, so a
+// short row still has many loads in flight; the partial sums meet in LDS and every wave finishes eight of the
+// rows. Result zero padded to RP columns.
 __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *X, int T, int K, const bf16_t *At, int r, int RP,
                                                           float scale, int n_out, const int *n_out_dev,
                                                           const int *in_block_of_out, const int *adapter_of_out, bf16_t *S)
 {
+    __shared__ float red[4][16][64];
     const int subs = (T + 31) / 32;
-    const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int ob = w / subs, sub = w % subs;
+    const int ob = blockIdx.x / subs, sub = blockIdx.x % subs;
     const int n = n_out_dev ? min(*n_out_dev, n_out) : n_out;
     if (ob >= n) return;
     const int k_ad = adapter_of_out[ob];
     if (k_ad < 0) return;
     const int xb = in_block_of_out ? in_block_of_out[ob] : ob;
-    const int lane = threadIdx.x & 63, lm = lane & 31, lh = lane >> 5;
+    const int q = threadIdx.x >> 6, lane = threadIdx.x & 63, lm = lane & 31, lh = lane >> 5;
     const int t = sub * 32 + lm;
-    const bf16_t *xr = X + ((size_t)xb * T + min(t, T - 1)) * K;
+    const bf16_t *xr = X + ((size_t)xb * T + min(t, T - 1)) * K + lh * 8;
     const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int steps = (K + 15) / 16, per = (steps + 3) / 4;
+    const int s0 = q * per, s1 = min(steps, s0 + per);
     for (int j0 = 0; j0 < RP; j0 += 32) {
         const int j = j0 + lm;
-        const bf16_t *ar = At + ((size_t)k_ad * r + min(j, r - 1)) * K;
+        const bf16_t *ar = At + ((size_t)k_ad * r + min(j, r - 1)) * K + lh * 8;
         f32x16 acc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-        for (int k0 = 0; k0 < K; k0 += 16) {
-            const int k = k0 + lh * 8;
-            const bool kin = k + 8 <= K;
+        int st = s0;
+        for (; st + 4 <= s1; st += 4) {
+            bf16x8 fa[4], fb[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int k = (st + u) * 16;
+                const bool kin = k + lh * 8 + 8 <= K;
+                fa[u] = (t < T && kin) ? *(const bf16x8 *)(xr + k) : zero8;
+                fb[u] = (j < r && kin) ? *(const bf16x8 *)(ar + k) : zero8;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u], fb[u], acc, 0, 0, 0);
+        }
+        for (; st < s1; ++st) {
+            const int k = st * 16;
+            const bool kin = k + lh * 8 + 8 <= K;
             const bf16x8 fa = (t < T && kin) ? *(const bf16x8 *)(xr + k) : zero8;
             const bf16x8 fb = (j < r && kin) ? *(const bf16x8 *)(ar + k) : zero8;
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
         }
+        if (j0) __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 16; ++e) red[q][e][lane] = acc[e];
+        __syncthreads();
         if (j < RP) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int tt = sub * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-                if (tt < T) S[((size_t)ob * T + tt) * RP + j] = (bf16_t)(scale * acc[e]);
+            for (int i = 0; i < 4; ++i) {
+                const int e = 4 * q + i;
+                const float v = red[0][e][lane] + red[1][e][lane] + red[2][e][lane] + red[3][e][lane];
+                const int tt = sub * 32 + 8 * q + 4 * lh + i;
+                if (tt < T) S[((size_t)ob * T + tt) * RP + j] = (bf16_t)(scale * v);
             }
         }
     }
@@ -352,7 +375,7 @@ int launch_shrink(const void *X, int T, int K, const void *At, int r, int RP, fl
     if (dtype == POLY_BF16) {
         if (K % 8 != 0) return POLY_EINVAL;
         const int subs = (T + 31) / 32;
-        const unsigned blocks = (unsigned)(((size_t)n_out * subs + 3) / 4);
+        const unsigned blocks = (unsigned)((size_t)n_out * subs);
         POLY_LAUNCH(POLY_STAGE_SHRINK, shrink_bf16_kernel, dim3(blocks), dim3(256), st, (const bf16_t *)X, T, K, (const bf16_t *)At, r, RP, scale, n_out,
                            n_out_dev, in_block_of_out, adapter_of_out, (bf16_t *)S);
     } else {

@@ -60,6 +60,19 @@ def test_row_kernels_all_widths(D, heads, Dm, hw, r, targets, L0):
     compare(cfg, w, frames, off, ids, L0, K=cfg.n_adapters * cfg.C)
 
 
+@pytest.mark.parametrize("D,heads,Dm,hw,r,targets,L0", [
+    (256, 4, 512, 40, 8, 15, 0),    # LayerNorm rows of one 16-byte piece per lane; shrink over K = 256 and 512
+    (512, 8, 1024, 48, 16, 15, 1),  # two pieces per lane; T = 37
+    (320, 5, 640, 40, 4, 15, 0),    # D not a multiple of 256: the strided LayerNorm; shrink with 20 and 40 K steps (5 and 10 per wave)
+    (256, 4, 1024, 72, 16, 3, 0),   # adapters on qkv and proj only: the layer splits into GEMM kernels without the feed-forward shrink
+])
+def test_wide_path_widths(D, heads, Dm, hw, r, targets, L0):
+    """bf16 models wider than the fused row kernels: LayerNorm, shrink, GEMM and attention kernels at other widths than ViT-base's."""
+    cfg, w, frames, off, ids = synth.make_small_case(90 + D + r, dtype=synth.DT_BF16, targets=targets, L=2, F=5, r=r, max_set=3,
+                                                      n_adapters=4, D=D, heads=heads, Dm=Dm, hw=hw, patch=8)
+    compare(cfg, w, frames, off, ids, L0, K=cfg.n_adapters * cfg.C)
+
+
 @pytest.mark.parametrize("D,heads,Dm,hw,r,targets,L0", [(64, 1, 192, 64, 16, 1, 1), (128, 2, 384, 64, 8, 3, 0), (192, 3, 768, 40, 8, 3, 2)])
 def test_row_kernels_repeat_bitwise(D, heads, Dm, hw, r, targets, L0):
     """The fused row kernels hand LDS stages from a stream wave to the computing waves by hand-counted waits: a stage that is

@@ -287,10 +287,12 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
     const int nk = g.K / BK;
     const int npro = min(NS, nk);
     for (int s = 0; s < npro; ++s) issue(s, s);
-    const int n_in = g.n_in_dev ? min(*g.n_in_dev, g.n_in) : g.n_in;
+    const bool flat = g.Tb > 0;                            // one run of rows over all blocks: xb = 0, t0 = first row of the tile
+    const int n_in = flat ? 1 : (g.n_in_dev ? min(*g.n_in_dev, g.n_in) : g.n_in);
+    const int Tlim = flat ? (g.n_in_dev ? min(*g.n_in_dev, g.nb) : g.nb) * g.Tb : g.T;   // rows that exist
     int ob0 = xb, ob1 = xb + 1;
     if (g.out_off && xb < n_in) { ob0 = g.out_off[xb]; ob1 = g.out_off[xb + 1]; }
-    if (xb >= n_in || ob0 >= ob1) {
+    if (xb >= n_in || ob0 >= ob1 || t0 >= Tlim) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         return;
     }
@@ -341,7 +343,7 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
     const bool has_lora = g.S && g.adapter_of_out;
     bf16x8 fs0[MI], fw0[NJ];
     int k_ad0 = -1;
-    if (EARLY && has_lora) {
+    if (EARLY && has_lora && !flat) {
         k_ad0 = g.adapter_of_out[ob0];
         if (k_ad0 >= 0) { load_fs(fs0, ob0, 0); load_fw(fw0, k_ad0, 0); }
     }
@@ -391,7 +393,7 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
     const bool gelu = g.mode == EPI_GELU;
 
     for (int ob = ob0; ob < ob1; ++ob) {
-        const int k_ad = has_lora ? g.adapter_of_out[ob] : -1;
+        const int k_ad = has_lora && !flat ? g.adapter_of_out[ob] : -1;
         const int rb = (g.mode == EPI_RESID && g.res) ? (g.res_block_of_out ? g.res_block_of_out[ob] : ob) : 0;
         bf16x8 fs[MI], fw[NJ];
         if (k_ad >= 0) {
@@ -407,10 +409,33 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
             const int tw = t0 + wm * MI * 32 + i * 32;     // first row of this 32-row subtile
-            if (tw >= g.T) break;
+            if (tw >= Tlim) break;
             f32x16 c[NJ];
 #pragma unroll
             for (int j = 0; j < NJ; ++j) c[j] = acc[i][j];
+            if (flat && has_lora) {
+                // the 32 rows of this subtile lie in block ba and, from row `split` on, in block ba + 1 (blocks are longer
+                // than a subtile or the split is handled block by block): one expand per block, fed with the S rows of that
+                // block only
+                const int ba = tw / g.Tb;
+                int lo = 0;
+                for (int bb = ba; lo < 32 && bb * g.Tb < Tlim; ++bb) {     // (blocks past the true count have no valid adapter id)
+                    const int hi = min(32, (bb + 1) * g.Tb - tw);        // rows [lo, hi) of the subtile belong to block bb
+                    const int k_b = g.adapter_of_out[bb];
+                    if (k_b >= 0) {
+                        for (int s0 = 0; s0 < g.RP; s0 += 16) {
+                            const int t = min(tw + lm, g.T - 1);
+                            bf16x8 fsb = *(const bf16x8 *)((const bf16_t *)g.S + (size_t)t * g.RP + s0 + lh * 8);
+                            if (lm < lo || lm >= hi) fsb = zero8;
+                            bf16x8 fwb[NJ];
+                            load_fw(fwb, k_b, s0);
+#pragma unroll
+                            for (int j = 0; j < NJ; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwb[j], fsb, c[j], 0, 0, 0);
+                        }
+                    }
+                    lo = hi;
+                }
+            }
             if (k_ad >= 0) {
                 // low-rank expand: one more MFMA K step per 16 ranks
                 if (!EARLY) {   // large tiles are short of registers: operands are fetched one subtile at a time
@@ -430,7 +455,7 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
             }
             // residual and position rows of this subtile: requested before the staging round trip when there are
             // registers for them, so that their latency overlaps it
-            const int rows_left = g.T - tw;
+            const int rows_left = Tlim - tw;
             const size_t obase = ((size_t)ob * g.Tout + g.t_off + tw) * g.N + col;
             const float *res = (g.mode == EPI_RESID && g.res) ? g.res + ((size_t)rb * g.Tout + g.t_off + tw) * g.N + col : nullptr;
             const float *pos = (g.mode == EPI_RESID && g.pos) ? g.pos + (size_t)(g.t_off + tw) * g.N + col : nullptr;
@@ -586,6 +611,25 @@ static void launch_dma(const GemmArgs &g, hipStream_t st)
     POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, kern, dim3(dma_grid(g.n_in * tiles_m, tiles_n)), dim3(64 * WM * WN), LDS, st, g, tiles_m, tiles_n);
 }
 
+static int launch_gemm_dma(const GemmArgs &g, hipStream_t st)
+{
+    // long contractions with many tiles: 256-row tiles cut the L2 -> LDS traffic per flop; short contractions (K = 192)
+    // and small batches keep 128-row tiles, whose workgroups are light enough to overlap their load latency and epilogues
+    // across a CU
+    const long tiles256 = (long)g.n_in * ((g.T + 255) / 256) * ((g.N + 255) / 256);
+    const bool big = g.T > 128 && g.K >= 512;
+    if (big && g.N % 256 == 0 && tiles256 >= 512) {
+        launch_dma<256, 256, 2, 4, 2>(g, st);
+    } else if (big && g.N % 128 == 0 && (long)g.n_in * ((g.T + 255) / 256) * ((g.N + 127) / 128) >= 512) {
+        launch_dma<256, 128, 4, 2, 2>(g, st);
+    } else if (g.N % 128 == 0 || g.N >= 1024) {
+        launch_dma<128, 128, 2, 2, 2>(g, st);
+    } else {
+        launch_dma<128, 64, 2, 2, 2>(g, st);
+    }
+    return hipGetLastError() == hipSuccess ? POLY_OK : POLY_EHIP;
+}
+
 int launch_gemm(const GemmArgs &g, int dtype, hipStream_t st)
 {
     if (g.n_in <= 0 || g.T <= 0) return POLY_OK;
@@ -593,21 +637,18 @@ int launch_gemm(const GemmArgs &g, int dtype, hipStream_t st)
         if (g.K % 8 != 0 || (g.S && g.RP % 16 != 0)) return POLY_EINVAL;
         if ((long)g.N * g.K > 0x7fffffffL || (long)g.T * g.K > 0x7fffffffL) return POLY_EINVAL;
         if (g.K % 64 == 0 && g.N % 8 == 0) {
-            // long contractions with many tiles: 256-row tiles (one per 197-token block) cut the L2 -> LDS traffic
-            // per flop; short contractions (K = 192) and small batches keep 128-row tiles, whose workgroups are
-            // light enough to overlap their load latency and epilogues across a CU
-            const long tiles256 = (long)g.n_in * ((g.T + 255) / 256) * ((g.N + 255) / 256);
-            const bool big = g.T > 128 && g.K >= 512;
-            if (big && g.N % 256 == 0 && tiles256 >= 512) {
-                launch_dma<256, 256, 2, 4, 2>(g, st);
-            } else if (big && g.N % 128 == 0 && (long)g.n_in * ((g.N + 127) / 128) >= 512) {
-                launch_dma<256, 128, 4, 2, 2>(g, st);
-            } else if (g.N % 128 == 0 || g.N >= 1024) {
-                launch_dma<128, 128, 2, 2, 2>(g, st);
-            } else {
-                launch_dma<128, 64, 2, 2, 2>(g, st);
+            // blocks that are stored back to back, each to its own rows, with nothing indexed by the row inside a block:
+            // the row tiles run over all blocks as one (a 197-row block fills only 77 % of a 256-row tile of its own)
+            GemmArgs gf = g;
+            const long rows = (long)g.n_in * g.T;
+            if (!g.out_off && g.Tout == g.T && g.t_off == 0 && !g.pos && !g.res_block_of_out && g.n_in > 1 && g.T % 256 != 0 &&
+                rows * g.K <= 0x7fffffffL && rows * g.N <= 0x7fffffffL) {
+                gf.Tb = g.T; gf.nb = g.n_in;
+                gf.T = gf.Tout = (int)rows; gf.n_in = 1;
             }
-        } else {
+            return launch_gemm_dma(gf, st);
+        }
+        {
             const int tiles_m = (g.T + 127) / 128;
             const bool wide = g.N % 128 == 0 || g.N >= 1024;
             const long blocks = (long)g.n_in * tiles_m * (wide ? (g.N + 127) / 128 : (g.N + 63) / 64);

@@ -9,6 +9,13 @@
 
 #include <stdlib.h>
 
+// phase timestamps for tuning; a test harness defines the macros before including this file
+#ifndef GM_TS
+#define GM_TS(i)
+#define GM_TS_END
+#define GM_TS_BYTES 0
+#endif
+
 namespace {
 
 template <typename T> __device__ __forceinline__ void epilogue_store_elt(const GemmArgs &g, int ob, int t, int col, float v)
@@ -203,9 +210,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_generic_kernel(const GemmArgs g
 // 16 ranks, stages fp32 rows through LDS with 16-byte writes and stores whole 128/256-byte row segments,
 // adding bias, residual and position rows with vector loads.
 //
-// Tile order: workgroup ids are dealt round-robin to the 8 XCDs, so id % 8 picks the XCD.  Each XCD owns a
-// contiguous range of row tiles and walks it once per panel of PANEL column tiles, which keeps one W panel
-// and the row tiles in flight inside that XCD's 4 MB L2 instead of streaming all of W past every row tile.
+// Tile order: workgroup ids are dealt round-robin to the 8 XCDs, so id % 8 picks the XCD.  The tiles, ordered by panel of
+// PANEL column tiles, then row tile, then column tile, are cut into eight equal runs, one per XCD: an XCD works on one
+// W panel at a time (it stays in that XCD's 4 MB L2 instead of all of W streaming past every row tile) and the XCDs
+// finish together (a ninth of a round more on one XCD is a whole round more for the kernel).
 #define POLY_GLDS16(gptr, lptr)                                                                          \
     __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(gptr),           \
                                      (void __attribute__((address_space(3))) *)(lptr), 16, 0, 0)
@@ -215,22 +223,23 @@ template <int N> __device__ __forceinline__ void wait_vm_and_barrier()
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-// (row tile, column tile) of workgroup `bid`; false if this workgroup has nothing to do
+// (row tile, column tile) of workgroup `bid`; false if this workgroup has nothing to do.  All tiles in the order (panel of
+// `panel` column tiles, row tile, column tile inside the panel) are cut into eight equal runs, one per XCD: a run covers one
+// or two W panels and a contiguous range of row tiles, and no XCD has more than one tile more than another.
 __device__ __forceinline__ bool xcd_tile(int bid, int tiles_mtot, int tiles_n, int panel, int &mt, int &tn)
 {
     const int xcd = bid & 7, j = bid >> 3;
-    const int per = (tiles_mtot + 7) >> 3;                 // row tiles per XCD
-    const int m_lo = xcd * per, m_cnt = min(per, tiles_mtot - m_lo);
-    if (m_cnt <= 0) return false;
-    const int full = m_cnt * panel;                        // workgroups per full panel
-    const int pn = j / full, rem = j - pn * full;
+    const long total = (long)tiles_mtot * tiles_n;
+    const long lo = total * xcd / 8, hi = total * (xcd + 1) / 8;
+    const long L = lo + j;
+    if (L >= hi) return false;
+    const long full = (long)tiles_mtot * panel;            // tiles per full panel
+    const int pn = (int)(L / full);
+    const int rem = (int)(L - pn * full);
     const int n_lo = pn * panel;
-    if (n_lo >= tiles_n) return false;
     const int width = min(panel, tiles_n - n_lo);
-    const int ml = rem / width;
-    if (ml >= m_cnt) return false;
-    mt = m_lo + ml;
-    tn = n_lo + rem - ml * width;
+    mt = rem / width;
+    tn = n_lo + rem - mt * width;
     return true;
 }
 
@@ -252,6 +261,7 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
 
     int mt, tn;
     if (!xcd_tile(blockIdx.x, g.n_in * tiles_m, tiles_n, PANEL, mt, tn)) return;
+    GM_TS(0);
     const int xb = mt / tiles_m, t0 = (mt - xb * tiles_m) * BM, n0 = tn * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -291,12 +301,13 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
     const int n_in = flat ? 1 : (g.n_in_dev ? min(*g.n_in_dev, g.n_in) : g.n_in);
     const int Tlim = flat ? (g.n_in_dev ? min(*g.n_in_dev, g.nb) : g.nb) * g.Tb : g.T;   // rows that exist
     int ob0 = xb, ob1 = xb + 1;
-    if (g.out_off && xb < n_in) { ob0 = g.out_off[xb]; ob1 = g.out_off[xb + 1]; }
+    if (g.out_off && !flat && xb < n_in) { ob0 = g.out_off[xb]; ob1 = g.out_off[xb + 1]; }
     if (xb >= n_in || ob0 >= ob1 || t0 >= Tlim) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         return;
     }
 
+    GM_TS(1);
     f32x16 acc[MI][NJ];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -375,7 +386,9 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
                 for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
         }
     }
+    GM_TS(2);
     __syncthreads();   // all loads have landed (vmcnt(0) above) and all waves are done with the tiles
+    GM_TS(3);
 
     // ---- epilogue, wave by wave and 32 rows at a time: no workgroup barrier is needed because each wave stages
     // through its own LDS region and the LDS executes one wave's instructions in order.
@@ -392,8 +405,92 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
     if (g.bias && col_ok) bias4 = *(const f32x4 *)(g.bias + col);
     const bool gelu = g.mode == EPI_GELU;
 
+    // one 32-row subtile of one output block: c -> LDS -> global.  Row 0 of the subtile is row trow0 of the block (negative
+    // when the block starts inside the subtile); rows [lo, hi) of the subtile are stored.
+    auto emit = [&](f32x16(&c)[NJ], int ob, int rb, int trow0, int lo, int hi) {
+        const long obase = ((long)ob * g.Tout + g.t_off + trow0) * g.N + col;
+        const float *res = (g.mode == EPI_RESID && g.res) ? g.res + ((long)rb * g.Tout + g.t_off + trow0) * g.N + col : nullptr;
+        const float *pos = (g.mode == EPI_RESID && g.pos) ? g.pos + (long)(g.t_off + trow0) * g.N + col : nullptr;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ch = j * 8 + 2 * q + lh;
+                const f32x4 v = {c[j][4 * q], c[j][4 * q + 1], c[j][4 * q + 2], c[j][4 * q + 3]};
+                *(f32x4 *)(stg + lm * (NC * 4) + ((ch ^ swz(lm)) << 2)) = v;
+            }
+        // LDS -> global
+        if (g.mode == EPI_RESID) {
+            float *out = (float *)g.out + obase;
+#pragma unroll 2
+            for (int q = 0; q < 32 / RPP; ++q) {
+                const int row = q * RPP + rrow;
+                if (row < lo || row >= hi || !col_ok) continue;
+                f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4;
+                if (res) v += *(const f32x4 *)(res + (long)row * g.N);
+                if (pos) v += *(const f32x4 *)(pos + (long)row * g.N);
+                *(f32x4 *)(out + (long)row * g.N) = v;
+            }
+        } else {
+            bf16_t *out = (bf16_t *)g.out + obase;
+#pragma unroll 2
+            for (int q = 0; q < 32 / RPP; ++q) {
+                const int row = q * RPP + rrow;
+                if (row < lo || row >= hi || !col_ok) continue;
+                f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4;
+                if (gelu) {
+#pragma unroll
+                    for (int z = 0; z < 4; ++z) v[z] = gelu_poly(v[z]);
+                }
+                const bf16x4 w = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+                *(bf16x4 *)(out + (long)row * g.N) = w;
+            }
+        }
+    };
+
+    if (flat) {
+        // Row tiles that ignore block boundaries.  The 32 rows of a subtile lie in one block or (a block being at least 32
+        // rows, else in several) in consecutive ones: block by block, every row-block that fans out of it gets its own
+        // expand, fed with the S rows of that row-block only, and stores its rows of the subtile.
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int tw = t0 + wm * MI * 32 + i * 32;     // first row of this 32-row subtile
+            if (tw >= Tlim) break;
+            int lo = 0;
+            for (int bb = tw / g.Tb; lo < 32 && bb * g.Tb < Tlim; ++bb) {   // (blocks past the true count have no valid ids)
+                const int trow0 = tw - bb * g.Tb;
+                const int hi = min(32, g.Tb - trow0);                       // rows [lo, hi) of the subtile belong to block bb
+                const int o0 = g.out_off ? g.out_off[bb] : bb, o1 = g.out_off ? g.out_off[bb + 1] : bb + 1;
+                for (int ob = o0; ob < o1; ++ob) {
+                    const int k_ad = has_lora ? g.adapter_of_out[ob] : -1;
+                    const int rb = (g.mode == EPI_RESID && g.res) ? (g.res_block_of_out ? g.res_block_of_out[ob] : ob) : 0;
+                    f32x16 c[NJ];
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) c[j] = acc[i][j];
+                    if (k_ad >= 0) {
+                        const int t = min(max(trow0 + lm, 0), g.Tb - 1);
+                        for (int s0 = 0; s0 < g.RP; s0 += 16) {
+                            bf16x8 fsb = *(const bf16x8 *)((const bf16_t *)g.S + ((size_t)ob * g.Tb + t) * g.RP + s0 + lh * 8);
+                            if (lm < lo || lm >= hi) fsb = zero8;
+                            bf16x8 fwb[NJ];
+                            load_fw(fwb, k_ad, s0);
+#pragma unroll
+                            for (int j = 0; j < NJ; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwb[j], fsb, c[j], 0, 0, 0);
+                        }
+                    }
+                    emit(c, ob, rb, trow0, lo, hi);
+                }
+                lo = hi;
+            }
+            if (i == MI / 2 - 1) GM_TS(4);
+        }
+        GM_TS(5);
+        GM_TS_END;
+        return;
+    }
+
     for (int ob = ob0; ob < ob1; ++ob) {
-        const int k_ad = has_lora && !flat ? g.adapter_of_out[ob] : -1;
+        const int k_ad = has_lora ? g.adapter_of_out[ob] : -1;
         const int rb = (g.mode == EPI_RESID && g.res) ? (g.res_block_of_out ? g.res_block_of_out[ob] : ob) : 0;
         bf16x8 fs[MI], fw[NJ];
         if (k_ad >= 0) {
@@ -409,33 +506,10 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
             const int tw = t0 + wm * MI * 32 + i * 32;     // first row of this 32-row subtile
-            if (tw >= Tlim) break;
+            if (tw >= g.T) break;
             f32x16 c[NJ];
 #pragma unroll
             for (int j = 0; j < NJ; ++j) c[j] = acc[i][j];
-            if (flat && has_lora) {
-                // the 32 rows of this subtile lie in block ba and, from row `split` on, in block ba + 1 (blocks are longer
-                // than a subtile or the split is handled block by block): one expand per block, fed with the S rows of that
-                // block only
-                const int ba = tw / g.Tb;
-                int lo = 0;
-                for (int bb = ba; lo < 32 && bb * g.Tb < Tlim; ++bb) {     // (blocks past the true count have no valid adapter id)
-                    const int hi = min(32, (bb + 1) * g.Tb - tw);        // rows [lo, hi) of the subtile belong to block bb
-                    const int k_b = g.adapter_of_out[bb];
-                    if (k_b >= 0) {
-                        for (int s0 = 0; s0 < g.RP; s0 += 16) {
-                            const int t = min(tw + lm, g.T - 1);
-                            bf16x8 fsb = *(const bf16x8 *)((const bf16_t *)g.S + (size_t)t * g.RP + s0 + lh * 8);
-                            if (lm < lo || lm >= hi) fsb = zero8;
-                            bf16x8 fwb[NJ];
-                            load_fw(fwb, k_b, s0);
-#pragma unroll
-                            for (int j = 0; j < NJ; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwb[j], fsb, c[j], 0, 0, 0);
-                        }
-                    }
-                    lo = hi;
-                }
-            }
             if (k_ad >= 0) {
                 // low-rank expand: one more MFMA K step per 16 ranks
                 if (!EARLY) {   // large tiles are short of registers: operands are fetched one subtile at a time
@@ -453,73 +527,11 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
                     for (int j = 0; j < NJ; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw2[j], fs2[i], c[j], 0, 0, 0);
                 }
             }
-            // residual and position rows of this subtile: requested before the staging round trip when there are
-            // registers for them, so that their latency overlaps it
-            const int rows_left = Tlim - tw;
-            const size_t obase = ((size_t)ob * g.Tout + g.t_off + tw) * g.N + col;
-            const float *res = (g.mode == EPI_RESID && g.res) ? g.res + ((size_t)rb * g.Tout + g.t_off + tw) * g.N + col : nullptr;
-            const float *pos = (g.mode == EPI_RESID && g.pos) ? g.pos + (size_t)(g.t_off + tw) * g.N + col : nullptr;
-            constexpr bool RES_EARLY = false;   // costs 16 registers and with them a resident workgroup per CU: not worth it
-            f32x4 rv[RES_EARLY ? 32 / RPP : 1];
-            if (RES_EARLY && g.mode == EPI_RESID) {
-#pragma unroll
-                for (int q = 0; q < 32 / RPP; ++q) {
-                    const int row = q * RPP + rrow;
-                    f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                    if (row < rows_left && col_ok) {
-                        if (res) v = *(const f32x4 *)(res + (size_t)row * g.N);
-                        if (pos) v += *(const f32x4 *)(pos + (size_t)row * g.N);
-                    }
-                    rv[RES_EARLY ? q : 0] = v;
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int ch = j * 8 + 2 * q + lh;
-                    const f32x4 v = {c[j][4 * q], c[j][4 * q + 1], c[j][4 * q + 2], c[j][4 * q + 3]};
-                    *(f32x4 *)(stg + lm * (NC * 4) + ((ch ^ swz(lm)) << 2)) = v;
-                }
-            // LDS -> global
-            if (g.mode == EPI_RESID) {
-                float *out = (float *)g.out + obase;
-                if (RES_EARLY) {
-#pragma unroll
-                    for (int q = 0; q < 32 / RPP; ++q) {
-                        const int row = q * RPP + rrow;
-                        if (row >= rows_left || !col_ok) continue;
-                        const f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4 + rv[RES_EARLY ? q : 0];
-                        *(f32x4 *)(out + (size_t)row * g.N) = v;
-                    }
-                } else {
-#pragma unroll 2
-                    for (int q = 0; q < 32 / RPP; ++q) {
-                        const int row = q * RPP + rrow;
-                        if (row >= rows_left || !col_ok) continue;
-                        f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4;
-                        if (res) v += *(const f32x4 *)(res + (size_t)row * g.N);
-                        if (pos) v += *(const f32x4 *)(pos + (size_t)row * g.N);
-                        *(f32x4 *)(out + (size_t)row * g.N) = v;
-                    }
-                }
-            } else {
-                bf16_t *out = (bf16_t *)g.out + obase;
-#pragma unroll 2
-                for (int q = 0; q < 32 / RPP; ++q) {
-                    const int row = q * RPP + rrow;
-                    if (row >= rows_left || !col_ok) continue;
-                    f32x4 v = *(const f32x4 *)(stg + row * (NC * 4) + ((rch ^ swz(row)) << 2)) + bias4;
-                    if (gelu) {
-#pragma unroll
-                        for (int z = 0; z < 4; ++z) v[z] = gelu_poly(v[z]);
-                    }
-                    const bf16x4 w = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
-                    *(bf16x4 *)(out + (size_t)row * g.N) = w;
-                }
-            }
+            emit(c, ob, rb, tw, 0, min(32, g.T - tw));
         }
+        GM_TS(ob == ob0 ? 4 : 5);
     }
+    GM_TS_END;
 }
 
 // ------------------------------------------------------------------ fp32 vector ALU
@@ -588,17 +600,17 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g)
 
 }  // namespace
 
-// grid of the XCD-panel order: every XCD gets ceil(row tiles / 8) row tiles x all column tiles
+// grid of the XCD order: every XCD gets ceil(tiles / 8) workgroups
 static unsigned dma_grid(int tiles_mtot, int tiles_n)
 {
-    const long per = (tiles_mtot + 7) / 8;
-    return (unsigned)(per * tiles_n * 8);
+    const long total = (long)tiles_mtot * tiles_n;
+    return (unsigned)((total + 7) / 8 * 8);
 }
 
 template <int BM, int BN, int WM, int WN, int NS>
 static void launch_dma(const GemmArgs &g, hipStream_t st)
 {
-    constexpr int LDS = NS * (BM + BN) * 64 * 2;
+    constexpr int LDS = NS * (BM + BN) * 64 * 2 + GM_TS_BYTES;
     auto kern = gemm_bf16_dma_kernel<BM, BN, WM, WN, NS>;
     if (LDS > 64 * 1024) {
         static bool attr_set = false;   // raising the dynamic LDS limit is a per-kernel, process-wide setting
@@ -637,14 +649,14 @@ int launch_gemm(const GemmArgs &g, int dtype, hipStream_t st)
         if (g.K % 8 != 0 || (g.S && g.RP % 16 != 0)) return POLY_EINVAL;
         if ((long)g.N * g.K > 0x7fffffffL || (long)g.T * g.K > 0x7fffffffL) return POLY_EINVAL;
         if (g.K % 64 == 0 && g.N % 8 == 0) {
-            // blocks that are stored back to back, each to its own rows, with nothing indexed by the row inside a block:
-            // the row tiles run over all blocks as one (a 197-row block fills only 77 % of a 256-row tile of its own)
+            // input blocks stored back to back and nothing but the output block indexed by the row inside a block: the row
+            // tiles run over all input blocks as one (a 197-row block fills only 77 % of a 256-row tile of its own)
             GemmArgs gf = g;
             const long rows = (long)g.n_in * g.T;
-            if (!g.out_off && g.Tout == g.T && g.t_off == 0 && !g.pos && !g.res_block_of_out && g.n_in > 1 && g.T % 256 != 0 &&
+            if (g.Tout == g.T && g.t_off == 0 && !g.pos && g.n_in > 1 && g.T % 256 != 0 &&
                 rows * g.K <= 0x7fffffffL && rows * g.N <= 0x7fffffffL) {
                 gf.Tb = g.T; gf.nb = g.n_in;
-                gf.T = gf.Tout = (int)rows; gf.n_in = 1;
+                gf.T = (int)rows; gf.n_in = 1;          // (Tout stays the block length: it places the output blocks)
             }
             return launch_gemm_dma(gf, st);
         }

@@ -159,9 +159,9 @@ struct GemmArgs {
     const float *res;     // EPI_RESID: float [..*Tout][N] added (row res_block*Tout + t_off + t), or null
     const int *res_block_of_out;  // null = ob
     const float *pos;     // EPI_RESID: float [Tout][N] added (row t_off + t), or null
-    // set by launch_gemm only.  Tb > 0: the nb blocks of Tb rows are tiled as ONE run of nb * Tb rows (T = Tout = nb * Tb,
-    // n_in = 1, n_in_dev still counts blocks), so that row tiles ignore block boundaries; the adapter of a row is that of
-    // block row / Tb
+    // set by launch_gemm only.  Tb > 0: the nb input blocks of Tb rows are tiled as ONE run of nb * Tb rows (T = nb * Tb,
+    // n_in = 1; n_in_dev still counts blocks and Tout = Tb still places the output blocks), so that row tiles ignore block
+    // boundaries; row t of the run belongs to input block t / Tb
     int Tb, nb;
 };
 

@@ -500,6 +500,12 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // By: the y tile is complete
         LY_TSS(201 + 10 * (wave - 4));
         add_tile();                                                             // x'' = x' + y
+        if (HAS_QKV) {
+            // Bt: the tile is dead.  Chunks 2-4 of C (stages 0-2) are requested now, by a computing wave: requested by a
+            // loader after its stores of x'', they would queue up behind those and arrive three thousand cycles into C.
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            last = max(last, NA + nch + min(nchq, 5) - 1);
+        }
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int row = xslot + 16 * k;
@@ -576,6 +582,11 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // Be: the ring positions of B are consumed
         LY_TS(9);
         asm volatile("s_barrier" ::: "memory");                                 // By
+        if (HAS_QKV) {
+            asm volatile("s_barrier" ::: "memory");                             // Bt
+            if (wave == 0)
+                for (int c = 2; c < min(nchq, 5); ++c) issue_item(NA + nch + c);
+        }
     }
     if (!HAS_QKV) return;
 
@@ -599,6 +610,12 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         if (lora_q) fs = shrink(a.r);
 #pragma unroll
         for (int s = 0; s < (LY_MAXCH + 1) / 2; ++s) {
+            // chunks 2-4 were requested by wave 0: it waits for its own loads (the other waves have none in flight)
+            if (s == 1) {
+                if (nchq >= 5) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NLD) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+            if (s == 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             // uniform conditions, written as guards (not a break) so that the loop unrolls and acc stays in registers
             if (2 * s + 1 < nchq) linear_step(acc[2 * s], acc[2 * s + 1], 2 * s, PC + 2 * s, Nq, bq_s, std::true_type{});
             else if (2 * s < nchq) linear_step(acc[2 * s], acc[2 * s], 2 * s, PC + 2 * s, Nq, bq_s, std::false_type{});

@@ -220,6 +220,54 @@ def select(scores, membership, theta: float = 0.5, context_copy: bool = False, a
     return off, ids[:n_rows.value].copy(), int(n_unc.value)
 
 
+# ------------------------------------- base head and the lagged loop (Fig. 3b)
+
+def trunk(cfg, w, frames, L0: Optional[int] = None):
+    """Residual stream of every frame after the shared layers [0, L0), which no adapter touches: [F, T, D].
+
+    The stages above applied in the order of the pre-LayerNorm block, one frame at a time.
+    """
+    L0 = cfg.L0 if L0 is None else L0
+    out = np.empty((len(frames), cfg.T, cfg.D))
+    for f, frame in enumerate(frames):
+        x = patch_embed(frame, cfg, w)
+        for l in range(L0):
+            u = layernorm(x, w["ln1_g"][l], w["ln1_b"][l], cfg.ln_eps)
+            o = attention(linear(u, w["qkv_w"][l], w["qkv_b"][l]), cfg.heads)
+            x = x + linear(o, w["proj_w"][l], w["proj_b"][l])
+            u = layernorm(x, w["ln2_g"][l], w["ln2_b"][l], cfg.ln_eps)
+            x = x + linear(gelu(linear(u, w["fc1_w"][l], w["fc1_b"][l])), w["fc2_w"][l], w["fc2_b"][l])
+        out[f] = x
+    return out
+
+
+def base_head(cfg, w, frames, base_w, base_b, L0: Optional[int] = None):
+    """Label scores of the base model's own head on the class token of the shared layers' output (the monitor
+    that drives the selection, Sec. 3.2 / Fig. 3b): sigmoid(LN_f(x[0]) base_w + base_b), [F, K]."""
+    x = trunk(cfg, w, frames, L0)[:, 0, :]
+    z = layernorm(x, w["lnf_g"], w["lnf_b"], cfg.ln_eps)
+    return 1.0 / (1.0 + np.exp(-linear(z, base_w, base_b)))
+
+
+def stream_step(cfg, w, frames, base_w, base_b, membership, carry, state: Optional[SelectState] = None,
+                L0: Optional[int] = None, theta: float = 0.5, context_copy: bool = False, acc=None, tau: float = 0.0,
+                K_merged: int = 0):
+    """One call of the lagged loop on consecutive frames of one stream: frame t runs with the adapters selected
+    (Alg. 2) from the base scores of frame t - 1; the first frame of the call uses `carry` (the base scores of the
+    last frame of the previous call; zeros = no previous frame, hence no labels and no adapters).
+
+    Returns dict(base_scores [F,K], carry [K], row_offsets, adapter_ids, n_uncovered, logits, scores, merged).
+    """
+    bs = base_head(cfg, w, frames, base_w, base_b, L0)
+    lagged = np.concatenate([np.asarray(carry, dtype=np.float64)[None, :], bs[:-1]], axis=0)
+    # the selection sees the scores in single precision, as the kernel that thresholds them does
+    off, ids, n_unc = select(lagged.astype(np.float32), membership, theta=theta, context_copy=context_copy, acc=acc, tau=tau,
+                             state=state)
+    out = forward(cfg, w, frames, off, ids, L0=L0, K=K_merged)
+    out.update(base_scores=bs, carry=bs[-1].copy(), row_offsets=off, adapter_ids=ids, n_uncovered=n_unc)
+    return out
+
+
 # ------------------------------------------------- shape accounting (Table 2)
 
 def count_params(cfg, n_classes_base_head: int = 0) -> int:

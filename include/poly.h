@@ -172,6 +172,50 @@ int poly_forward(const poly_model_desc *m, const poly_base_weights *base, const 
                  void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * poly_stream_step -- the inference loop of Fig. 3b on F consecutive frames of one stream, with the
+ * one-frame lag of Sec. 3.2 (the adapters of a frame are chosen from the labels seen on the frame
+ * before), everything on the device:
+ *   layers [0, L0) once per frame;
+ *   base head on the class token of their output:
+ *       base_scores[t] = sigmoid(LN_f(x_t[0]) base_w^T + base_b)                 [F][K];
+ *   Alg. 2 (poly_select, same options and state) on the lagged scores
+ *       (carry, base_scores[0], ..., base_scores[F-2])  ->  S_0 .. S_{F-1} as CSR arrays;
+ *   layers [L0, L), heads and merge as in poly_forward on those row-blocks;
+ *   carry = base_scores[F-1] for the next call.
+ * A zeroed carry means "no previous frame": no label is active and the first frame runs without
+ * adapters.
+ *
+ *   s              host struct below; base_w elt [K][D], base_b [K] float, group_membership [M][K]
+ *                  uint8, state as in poly_select (nullable), carry device [K] float, in/out.
+ *   R              capacity of adapter_ids and of the per-row-block outputs.  If the selection needs
+ *                  more rows, counters[0] > R reports it, dev_status becomes POLY_ERANGE and no
+ *                  row-block output is written.
+ *   row_offsets    [F+1] int32 out, adapter_ids [R] int32 out, counters [2] int32 out (poly_select).
+ *   out_base_scores [F][K] float, nullable.  out_logits / out_scores [R][C], out_merged [F][K]
+ *                  (label space of the base head; needs heads->class_map) as in poly_forward.
+ *   workspace      >= poly_stream_step_workspace_bytes(m, F, R, K) bytes, 256-byte aligned.
+ * Errors as poly_forward and poly_select.
+ */
+typedef struct poly_stream {
+    const void *base_w;  /* elt [K][D] */
+    const float *base_b; /* [K] */
+    int32_t K;           /* labels, <= POLY_MAX_LABELS */
+    int32_t M;           /* contexts = adapters that can be selected, <= POLY_MAX_CONTEXTS */
+    const uint8_t *group_membership; /* device [M][K] */
+    poly_select_opts opts;
+    void *state;  /* device, poly_select_state_bytes(K) bytes, or NULL */
+    float *carry; /* device [K] */
+} poly_stream;
+
+size_t poly_stream_step_workspace_bytes(const poly_model_desc *m, int F, int R, int K);
+
+int poly_stream_step(const poly_model_desc *m, const poly_base_weights *base, const poly_lora_weights *lora,
+                     const poly_heads *heads, const poly_stream *s, const void *frames, int F, int R,
+                     int32_t *row_offsets, int32_t *adapter_ids, int32_t *counters, float *out_base_scores,
+                     float *out_logits, float *out_scores, float *out_merged, int32_t *dev_status,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * poly_lora_linear -- one multi-adapter linear in isolation (Sec. 3.1: h = xW + xAB with the
  * adapters applied side by side on a shared W).  Row-block b = (X block f, adapter k):
  *       Y[b] = X[f] Wt^T + bias + scale * (X[f] At_k^T) Bt_k^T.

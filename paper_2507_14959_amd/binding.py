@@ -21,7 +21,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpoly.so")
 
 EXPORTS = ("poly_status_string", "poly_select_state_bytes", "poly_select", "poly_forward_workspace_bytes",
-           "poly_forward", "poly_lora_linear_workspace_bytes", "poly_lora_linear", "poly_profile_begin", "poly_profile_end")
+           "poly_forward", "poly_stream_step_workspace_bytes", "poly_stream_step", "poly_lora_linear_workspace_bytes",
+           "poly_lora_linear", "poly_profile_begin", "poly_profile_end")
 STAGES = ("select", "gemm", "shrink", "attention", "layernorm", "other")
 
 
@@ -47,6 +48,11 @@ class Heads(C.Structure):
 
 class SelectOpts(C.Structure):
     _fields_ = [("theta", C.c_float), ("context_copy", C.c_int32), ("acc", C.c_void_p), ("tau", C.c_float)]
+
+
+class Stream(C.Structure):
+    _fields_ = [("base_w", C.c_void_p), ("base_b", C.c_void_p), ("K", C.c_int32), ("M", C.c_int32),
+                ("group_membership", C.c_void_p), ("opts", SelectOpts), ("state", C.c_void_p), ("carry", C.c_void_p)]
 
 
 class Profile(C.Structure):
@@ -77,6 +83,13 @@ def lib():
         L.poly_forward.argtypes = [C.POINTER(ModelDesc), C.POINTER(BaseWeights), C.POINTER(LoraWeights), C.POINTER(Heads),
                                    C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.poly_stream_step_workspace_bytes.restype = C.c_size_t
+        L.poly_stream_step_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.c_int, C.c_int, C.c_int]
+        L.poly_stream_step.restype = C.c_int
+        L.poly_stream_step.argtypes = [C.POINTER(ModelDesc), C.POINTER(BaseWeights), C.POINTER(LoraWeights), C.POINTER(Heads),
+                                       C.POINTER(Stream), C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                       C.c_void_p]
         L.poly_lora_linear_workspace_bytes.restype = C.c_size_t
         L.poly_lora_linear_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]
         L.poly_lora_linear.restype = C.c_int
@@ -204,6 +217,42 @@ def poly_forward(model: DeviceModel, frames: torch.Tensor, row_offsets: torch.Te
                             _stream(stream))
     if check and rc != POLY_OK:
         raise PolyError(rc, "poly_forward")
+    return rc
+
+
+class DeviceStream:
+    """Device side of the lagged loop: base head [D, K] / [K] (paper orientation; transposed and converted here), context
+    membership [M, K], selection state and the carried scores (zeros = no previous frame)."""
+
+    def __init__(self, model: DeviceModel, base_w: np.ndarray, base_b: np.ndarray, membership: np.ndarray, theta: float = 0.5,
+                 context_copy: bool = False, device="cuda"):
+        K = base_w.shape[1]
+        self.K, self.M = K, membership.shape[0]
+        self.base_w = torch.from_numpy(np.ascontiguousarray(base_w.T)).to(device=device, dtype=_elt(model.cfg.dtype)).contiguous()
+        self.base_b = torch.from_numpy(np.ascontiguousarray(base_b, dtype=np.float32)).to(device)
+        self.membership = torch.from_numpy(np.ascontiguousarray(membership, dtype=np.uint8)).to(device)
+        self.state = torch.zeros(poly_select_state_bytes(K), dtype=torch.uint8, device=device)
+        self.carry = torch.zeros(K, dtype=torch.float32, device=device)
+        self.c = Stream(self.base_w.data_ptr(), self.base_b.data_ptr(), K, self.M, self.membership.data_ptr(),
+                        SelectOpts(theta, int(context_copy), None, 0.0), self.state.data_ptr(), self.carry.data_ptr())
+
+
+def poly_stream_step_workspace_bytes(model: DeviceModel, F: int, R: int, K: int) -> int:
+    return int(lib().poly_stream_step_workspace_bytes(C.byref(model.desc), F, R, K))
+
+
+def poly_stream_step(model: DeviceModel, s: DeviceStream, frames: torch.Tensor, R: int, row_offsets: torch.Tensor,
+                     adapter_ids: torch.Tensor, counters: torch.Tensor, out_scores: torch.Tensor, workspace: torch.Tensor,
+                     out_base_scores: Optional[torch.Tensor] = None, out_logits: Optional[torch.Tensor] = None,
+                     out_merged: Optional[torch.Tensor] = None, dev_status: Optional[torch.Tensor] = None, stream=None,
+                     check: bool = True) -> int:
+    """One call of the lagged loop (base head -> Alg. 2 -> adapted layers) on consecutive frames of one stream."""
+    rc = lib().poly_stream_step(C.byref(model.desc), C.byref(model.base), C.byref(model.lora), C.byref(model.heads), C.byref(s.c),
+                                _ptr(frames), frames.shape[0], R, _ptr(row_offsets), _ptr(adapter_ids), _ptr(counters),
+                                _ptr(out_base_scores), _ptr(out_logits), _ptr(out_scores), _ptr(out_merged), _ptr(dev_status),
+                                _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    if check and rc != POLY_OK:
+        raise PolyError(rc, "poly_stream_step")
     return rc
 
 

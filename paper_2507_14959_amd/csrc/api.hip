@@ -92,10 +92,19 @@ extern "C" size_t poly_forward_workspace_bytes(const poly_model_desc *m, int F, 
     return carve_forward(m, F, R, nullptr).bytes;
 }
 
-extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *base, const poly_lora_weights *lora,
-                            const poly_heads *heads, const void *frames, int F, const int32_t *row_offsets,
-                            const int32_t *adapter_ids, int R, float *out_logits, float *out_scores, float *out_merged, int K,
-                            int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream)
+namespace {
+// what poly_stream_step adds to the forward: the CSR arrays are written on the way (after the shared layers) instead of given
+struct StreamStep {
+    const poly_stream *s;
+    int32_t *row_offsets, *adapter_ids, *counters;
+    float *out_base_scores;
+    float *lag;        // [F + 1][K], in the workspace behind the forward's part
+};
+
+int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const poly_lora_weights *lora,
+                 const poly_heads *heads, const void *frames, int F, const int32_t *row_offsets,
+                 const int32_t *adapter_ids, int R, float *out_logits, float *out_scores, float *out_merged, int K,
+                 int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream, const StreamStep *ss)
 {
     POLY_TRY(check_model(m));
     if (!base || !heads || F < 0 || R < 0) return POLY_EINVAL;
@@ -122,8 +131,22 @@ extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *b
     // tokens: x[f][0] = cls + pos[0]; x[f][1 + t] = patch_t W_pe + b_pe + pos[1 + t].  The same launch checks the CSR arrays and
     // builds the row maps (nothing before the first adapted layer needs them).
     POLY_TRY(launch_im2col(frames, w.patches, F, m->H, m->W, m->patch, dt, w.xa, base->cls, base->pos, T, D, out_merged,
-                           out_merged ? (size_t)F * K : 0, row_offsets, adapter_ids, R, m->n_adapters, w.meta, w.frame_of_row,
+                           out_merged ? (size_t)F * K : 0, ss ? nullptr : row_offsets, adapter_ids, R, m->n_adapters, w.meta, w.frame_of_row,
                            w.adapter_of_row, dev_status, st));
+    // The lagged loop: after the shared layers the base head scores the frames, Alg. 2 turns the scores of frame t - 1 into
+    // the adapter set of frame t, and the CSR check builds the row maps -- all on this stream, no host in between.
+    bool selected = ss == nullptr;
+    auto select_now = [&]() -> int {
+        selected = true;
+        const poly_stream *s = ss->s;
+        POLY_TRY(launch_base_head(w.xa, T, D, base->lnf_g, base->lnf_b, m->ln_eps, s->base_w, s->base_b, s->K, F, ss->lag,
+                                  ss->out_base_scores, s->carry, dt, st));
+        POLY_TRY(poly_select(ss->lag, F, s->K, s->group_membership, s->M, &s->opts, s->state, ss->row_offsets, ss->adapter_ids, R,
+                             ss->counters, stream));
+        if (hipMemcpyAsync(s->carry, ss->lag + (size_t)F * s->K, sizeof(float) * (size_t)s->K, hipMemcpyDeviceToDevice, st) != hipSuccess)
+            return POLY_EHIP;
+        return launch_prep(ss->row_offsets, ss->adapter_ids, F, R, m->n_adapters, w.meta, w.frame_of_row, w.adapter_of_row, dev_status, st);
+    };
     {
         GemmArgs g = {};
         g.A = w.patches; g.Wt = base->patch_w; g.bias = base->patch_b;
@@ -134,6 +157,7 @@ extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *b
 
     bool qkv_done = false;                     // the qkv linear of layer l was computed by layer l - 1's row kernel
     for (int l = 0; l < m->L; ++l) {
+        if (l == m->L0 && !selected) POLY_TRY(select_now());
         const bool lora_on = l >= m->L0 && R > 0;
         if (l >= m->L0 && R == 0) break;
         const bool fan = l == m->L0;           // first adapted layer: frames fan out into row-blocks
@@ -276,12 +300,52 @@ extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *b
         }
     }
 
+    if (!selected) POLY_TRY(select_now());        // (L0 == L: the shared layers are the whole backbone)
     if (R > 0) {
         POLY_TRY(launch_head(adapted ? w.xb : w.xa, adapted ? nullptr : w.frame_of_row, T, D, base->lnf_g, base->lnf_b, m->ln_eps,
                              heads->head_w, heads->head_b, m->C, w.adapter_of_row, w.frame_of_row, heads->class_map, K, w.meta, R,
                              out_logits, out_scores, out_merged, dt, st));
     }
     return POLY_OK;
+}
+}  // namespace
+
+extern "C" int poly_forward(const poly_model_desc *m, const poly_base_weights *base, const poly_lora_weights *lora,
+                            const poly_heads *heads, const void *frames, int F, const int32_t *row_offsets,
+                            const int32_t *adapter_ids, int R, float *out_logits, float *out_scores, float *out_merged, int K,
+                            int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return forward_impl(m, base, lora, heads, frames, F, row_offsets, adapter_ids, R, out_logits, out_scores, out_merged, K, dev_status,
+                        workspace, workspace_bytes, stream, nullptr);
+}
+
+static size_t stream_lag_offset(const poly_model_desc *m, int F, int R)
+{
+    return (carve_forward(m, F, R, nullptr).bytes + 255) & ~(size_t)255;
+}
+
+extern "C" size_t poly_stream_step_workspace_bytes(const poly_model_desc *m, int F, int R, int K)
+{
+    if (check_model(m) != POLY_OK || F < 0 || R < 0 || K <= 0) return 0;
+    return stream_lag_offset(m, F, R) + sizeof(float) * (size_t)(F + 1) * K;
+}
+
+extern "C" int poly_stream_step(const poly_model_desc *m, const poly_base_weights *base, const poly_lora_weights *lora,
+                                const poly_heads *heads, const poly_stream *s, const void *frames, int F, int R,
+                                int32_t *row_offsets, int32_t *adapter_ids, int32_t *counters, float *out_base_scores,
+                                float *out_logits, float *out_scores, float *out_merged, int32_t *dev_status, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    POLY_TRY(check_model(m));
+    if (!s || !s->base_w || !s->base_b || !s->group_membership || !s->carry || !counters) return POLY_EINVAL;
+    if (s->K <= 0 || s->K > POLY_MAX_LABELS || s->M <= 0 || s->M > POLY_MAX_CONTEXTS || s->M > m->n_adapters) return POLY_EINVAL;
+    if (F < 0 || R < 0) return POLY_EINVAL;
+    if (F == 0) return POLY_OK;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0) return POLY_EINVAL;
+    if (workspace_bytes < poly_stream_step_workspace_bytes(m, F, R, s->K)) return POLY_ECAP;
+    StreamStep ss = {s, row_offsets, adapter_ids, counters, out_base_scores, (float *)((char *)workspace + stream_lag_offset(m, F, R))};
+    return forward_impl(m, base, lora, heads, frames, F, row_offsets, adapter_ids, R, out_logits, out_scores, out_merged, s->K, dev_status,
+                        workspace, workspace_bytes, stream, &ss);
 }
 
 // ------------------------------------------------------------------ isolated multi-LoRA linear

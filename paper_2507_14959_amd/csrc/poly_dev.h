@@ -263,6 +263,9 @@ int launch_prep(const int32_t *row_offsets, const int32_t *adapter_ids, int F, i
 int launch_im2col(const void *frames, void *patches, int F, int H, int W, int p, int dtype, float *x, const float *cls, const float *pos,
                   int T_tok, int D, float *merged, size_t n_merged, const int32_t *row_offsets, const int32_t *adapter_ids, int R_cap,
                   int n_adapters, PolyMeta *meta, int32_t *frame_of_row, int32_t *adapter_of_row, int32_t *dev_status, hipStream_t st);
+// base head of the lagged loop: scores of frame f -> lag[f + 1][K] and out[f][K] (nullable); lag[0] = carry (or zeros)
+int launch_base_head(const float *x, int T, int D, const float *gain, const float *shift, float eps, const void *Wb, const float *bb,
+                     int K, int F, float *lag, float *out, const float *carry, int dtype, hipStream_t st);
 int launch_head(const float *x, const int *src_block_of_row, int T, int D, const float *gain, const float *shift, float eps,
                 const void *head_w, const float *head_b, int C, const int *adapter_of_row, const int *frame_of_row,
                 const int32_t *class_map, int K, const PolyMeta *meta, int R_cap, float *logits, float *scores, float *merged, int dtype,

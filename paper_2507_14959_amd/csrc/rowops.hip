@@ -405,6 +405,61 @@ static void launch_head_t(int nx, dim3 grid, hipStream_t st, const float *x, con
 #undef HEAD_CASE
 }
 
+// ------------------------------------------------------------------ base head of the lagged loop
+// Block f: LayerNorm of frame f's class token (row 0 of its block of x) and the K label scores
+// sigmoid(z Wb[c] + bb[c]); wave w takes classes w, w + 4, ...  The scores go to lag[f + 1] (the selection of frame
+// f + 1 reads them there) and to out[f]; block 0 also copies the carried scores of the previous call to lag[0].
+template <typename T>
+__global__ __launch_bounds__(256) void base_head_kernel(const float *x, int T_tok, int D, const float *gain, const float *shift, float eps,
+                                                        const T *Wb, const float *bb, int K, float *lag, float *out, const float *carry)
+{
+    extern __shared__ float bh_s[];      // z [D], then 8 partial sums
+    float *z = bh_s, *part = bh_s + D;
+    const int f = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float *xr = x + (size_t)f * T_tok * D;
+    if (f == 0)
+        for (int c = tid; c < K; c += 256) lag[c] = carry ? carry[c] : 0.f;
+    float s = 0.f;
+    for (int i = tid; i < D; i += 256) s += xr[i];
+    s = wave_sum(s);
+    if (lane == 0) part[wave] = s;
+    __syncthreads();
+    const float mean = (part[0] + part[1] + part[2] + part[3]) / D;
+    float q = 0.f;
+    for (int i = tid; i < D; i += 256) { const float d = xr[i] - mean; q += d * d; }
+    q = wave_sum(q);
+    if (lane == 0) part[4 + wave] = q;
+    __syncthreads();
+    const float inv = rsqrtf((part[4] + part[5] + part[6] + part[7]) / D + eps);
+    for (int i = tid; i < D; i += 256) z[i] = (xr[i] - mean) * inv * gain[i] + shift[i];
+    __syncthreads();
+    for (int c = wave; c < K; c += 4) {
+        const T *wr = Wb + (size_t)c * D;
+        float d = 0.f;
+        for (int i = lane; i < D; i += 64) d = fmaf(z[i], (float)wr[i], d);
+        d = wave_sum(d);
+        if (lane == 0) {
+            const float sc = 1.0f / (1.0f + expf(-(d + bb[c])));
+            lag[(size_t)(f + 1) * K + c] = sc;
+            if (out) out[(size_t)f * K + c] = sc;
+        }
+    }
+}
+
+int launch_base_head(const float *x, int T, int D, const float *gain, const float *shift, float eps, const void *Wb, const float *bb,
+                     int K, int F, float *lag, float *out, const float *carry, int dtype, hipStream_t st)
+{
+    if (F == 0) return POLY_OK;
+    const size_t lds = sizeof(float) * (size_t)(D + 8);
+    if (dtype == POLY_BF16)
+        POLY_LAUNCH_SHMEM(POLY_STAGE_OTHER, base_head_kernel<bf16_t>, dim3(F), dim3(256), lds, st, x, T, D, gain, shift, eps, (const bf16_t *)Wb, bb,
+                          K, lag, out, carry);
+    else
+        POLY_LAUNCH_SHMEM(POLY_STAGE_OTHER, base_head_kernel<float>, dim3(F), dim3(256), lds, st, x, T, D, gain, shift, eps, (const float *)Wb, bb,
+                          K, lag, out, carry);
+    return hip_ok();
+}
+
 // heads, and the merge to the label space when merged is given (zeroed by the caller, F x K)
 int launch_head(const float *x, const int *src_block_of_row, int T, int D, const float *gain, const float *shift, float eps,
                 const void *head_w, const float *head_b, int C, const int *adapter_of_row, const int *frame_of_row,

@@ -254,13 +254,14 @@ def make_lora_linear_case(n_xblocks: int = 256, T: int = 197, Kdim: int = 768, N
 # label stream (config 4)
 # ----------------------------------------------------------------------------
 
-def make_base_head(cfg: ModelCfg, K: int, seed: int, logit_std: float = 3.0) -> Tuple[np.ndarray, np.ndarray]:
+def make_base_head(cfg: ModelCfg, K: int, seed: int, logit_std: float = 3.0, bias_mean: float = -1.0) -> Tuple[np.ndarray, np.ndarray]:
     """Weights [D, K] and bias [K] of a base head over K labels.  The LayerNorm output it reads has unit variance per
-    element, so weights ~ N(0, logit_std^2 / D) give logits of about that spread: a few labels per frame are active
-    and the active set changes from frame to frame."""
+    element, so weights ~ N(0, logit_std^2 / D) give logits of about that spread around bias_mean: a few labels per
+    frame are active (bias_mean = -5 with 80 labels: about four, close to the paper's streams) and the active set
+    changes from frame to frame."""
     rng = np.random.default_rng(seed)
     W = _n(rng, (cfg.D, K), logit_std / np.sqrt(cfg.D))
-    b = _n(rng, (K,), 0.5, -1.0)
+    b = _n(rng, (K,), 0.5, bias_mean)
     if cfg.dtype == DT_BF16:
         W, b = round_to_bf16(W), round_to_bf16(b)
     return W, b

@@ -1,0 +1,135 @@
+"""poly_stream_step (base head -> Alg. 2 with a one-frame lag -> adapted layers) on the GPU against the CPU checker.
+
+The adapter sets are integer results decided by `score >= theta` on floating-point scores.  Wherever the checker's own
+scores keep a margin to theta that is larger than the error bound of the kernel's scores, the sets must agree exactly;
+the cases are built (seeded) so that this holds for every frame in fp32, and the assertion on the margin uses the
+checker's values only.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2507_14959_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {synth.DT_F32: 1e-4, synth.DT_BF16: 2e-2}
+
+
+def run_calls(cfg, w, bw, bb, mem, chunks, L0, R_cap, K):
+    dev = "cuda"
+    model = binding.DeviceModel(cfg, w, L0=L0)
+    s = binding.DeviceStream(model, bw, bb, mem)
+    outs = []
+    for frames_np in chunks:
+        F = frames_np.shape[0]
+        frames = model.frames_to_device(frames_np)
+        off = torch.full((F + 1,), -1, dtype=torch.int32, device=dev)
+        ids = torch.full((max(R_cap, 1),), -1, dtype=torch.int32, device=dev)
+        counters = torch.zeros(2, dtype=torch.int32, device=dev)
+        status = torch.zeros(1, dtype=torch.int32, device=dev)
+        scores = torch.zeros(max(R_cap, 1), cfg.C, device=dev)
+        logits = torch.zeros(max(R_cap, 1), cfg.C, device=dev)
+        base = torch.zeros(F, K, device=dev)
+        merged = torch.full((F, K), -1.0, device=dev)
+        ws = torch.empty(binding.poly_stream_step_workspace_bytes(model, F, R_cap, K), dtype=torch.uint8, device=dev)
+        binding.poly_stream_step(model, s, frames, R_cap, off, ids, counters, scores, ws, out_base_scores=base, out_logits=logits,
+                                 out_merged=merged, dev_status=status)
+        torch.cuda.synchronize()
+        outs.append(dict(off=off.cpu().numpy(), ids=ids.cpu().numpy(), counters=counters.cpu().numpy(), status=int(status.item()),
+                         scores=scores.cpu().numpy(), logits=logits.cpu().numpy(), base=base.cpu().numpy(), merged=merged.cpu().numpy(),
+                         carry=s.carry.cpu().numpy()))
+    return outs
+
+
+def check_stream(dtype, seed, L0, D=128, heads=2, Dm=256, L=3, n_calls=3, F=4, exact=True):
+    n_ad, gsz = 4, 3
+    K = n_ad * gsz
+    cfg, w, _, _, _ = synth.make_small_case(seed, dtype=dtype, targets=3, L=L, F=1, r=8, n_adapters=n_ad, D=D, heads=heads, Dm=Dm,
+                                             hw=40, patch=8, C=gsz)
+    frames = synth.make_frames(cfg, n_calls * F, np.random.default_rng(seed + 1))
+    mem = synth.make_group_membership(n_ad, gsz)
+    bw, bb = synth.make_base_head(cfg, K, seed + 2)
+    chunks = [frames[i * F:(i + 1) * F] for i in range(n_calls)]
+    got = run_calls(cfg, w, bw, bb, mem, chunks, L0, R_cap=F * n_ad, K=K)
+    st = oracle.SelectState(K, n_ad)
+    carry = np.zeros(K)
+    n_rows = 0
+    for c, g in zip(chunks, got):
+        want = oracle.stream_step(cfg, w, c, bw, bb, mem, carry, st, L0=L0, K_merged=K)
+        assert g["status"] == 0
+        assert np.abs(g["base"] - want["base_scores"]).max() < TOL[dtype]
+        assert np.abs(g["carry"] - want["carry"]).max() < TOL[dtype]
+        lagged = np.concatenate([carry[None], want["base_scores"][:-1]])
+        margin = np.abs(lagged - 0.5).min(axis=1)                       # per frame, from the checker's values only
+        safe = margin > 2 * TOL[dtype]
+        if exact:
+            assert safe.all(), "the seeded case must keep every score away from the threshold"
+        R = int(want["row_offsets"][-1])
+        if safe.all():
+            assert np.array_equal(g["off"], want["row_offsets"])
+            assert np.array_equal(g["ids"][:R], want["adapter_ids"])
+            assert g["counters"][0] == R and g["counters"][1] == want["n_uncovered"]
+            if R:
+                assert np.abs(g["logits"][:R] - want["logits"]).max() < TOL[dtype]
+                assert np.abs(g["scores"][:R] - want["scores"]).max() < TOL[dtype]
+            assert np.abs(g["merged"] - want["merged"]).max() < TOL[dtype]
+            n_rows += R
+        else:
+            # frames before the first unsafe one still have to agree
+            first = int(np.argmin(safe))
+            assert np.array_equal(g["off"][:first + 1], want["row_offsets"][:first + 1])
+            break
+        carry = want["carry"]
+    return n_rows
+
+
+@pytest.mark.parametrize("L0,seed", [(0, 300), (1, 301), (2, 306), (3, 303)])   # seeds whose scores all keep > 2e-3 from theta
+def test_stream_step_fp32_matches_checker_exactly(L0, seed):
+    assert check_stream(synth.DT_F32, seed, L0) > 0
+
+
+@pytest.mark.parametrize("seed,L0,D,heads,Dm", [(310, 2, 192, 3, 384), (311, 1, 256, 4, 512)])
+def test_stream_step_bf16(seed, L0, D, heads, Dm):
+    check_stream(synth.DT_BF16, seed, L0, D=D, heads=heads, Dm=Dm, exact=False)
+
+
+def test_stream_step_deit_tiny_placement_of_the_paper():
+    """Config-2 model, adapters on the last two layers (L0 = 10), 80 labels in 16 contexts of 5: two calls of four frames.
+    Seed 78 gives three active labels per frame, all scores > 0.13 away from theta (checked below on the checker's values)."""
+    cfg, w, frames, _, _ = synth.make_forward_case(2)
+    K, n_ctx = 80, 16
+    mem = synth.make_group_membership(n_ctx, 5)
+    bw, bb = synth.make_base_head(cfg, K, 78, bias_mean=-5.0)
+    chunks = [frames[0:4], frames[4:8]]
+    got = run_calls(cfg, w, bw, bb, mem, chunks, 10, R_cap=4 * 6, K=K)
+    st = oracle.SelectState(K, n_ctx)
+    carry = np.zeros(K)
+    total = 0
+    for c, g in zip(chunks, got):
+        want = oracle.stream_step(cfg, w, c, bw, bb, mem, carry, st, L0=10, K_merged=K)
+        lagged = np.concatenate([carry[None], want["base_scores"][:-1]])
+        assert np.abs(lagged - 0.5).min() > 2 * TOL[synth.DT_BF16]
+        R = int(want["row_offsets"][-1])
+        assert g["status"] == 0
+        assert np.abs(g["base"] - want["base_scores"]).max() < TOL[synth.DT_BF16]
+        assert np.array_equal(g["off"], want["row_offsets"]) and np.array_equal(g["ids"][:R], want["adapter_ids"])
+        assert np.abs(g["scores"][:R] - want["scores"]).max() < TOL[synth.DT_BF16]
+        assert np.abs(g["merged"] - want["merged"]).max() < TOL[synth.DT_BF16]
+        carry = want["carry"]
+        total += R
+    assert total > 0
+
+
+def test_stream_step_over_capacity_reports_and_writes_no_rows():
+    n_ad, gsz = 4, 3
+    K = n_ad * gsz
+    cfg, w, _, _, _ = synth.make_small_case(320, dtype=synth.DT_F32, targets=3, L=2, F=1, r=4, n_adapters=n_ad, hw=32, patch=8, C=gsz)
+    frames = synth.make_frames(cfg, 6, np.random.default_rng(5))
+    mem = synth.make_group_membership(n_ad, gsz)
+    bw, bb = synth.make_base_head(cfg, K, 9)
+    bb = bb + 6.0                                                        # every label active: every frame after the first wants all 4 adapters
+    got = run_calls(cfg, w, bw, bb, mem, [frames], L0=1, R_cap=5, K=K)[0]
+    assert got["counters"][0] == 5 * n_ad and got["status"] != 0
+    assert np.all(got["scores"] == 0)

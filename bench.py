@@ -248,7 +248,29 @@ def main():
         torch.cuda.synchronize()
         extra["stream_cfg4"] = {"frames_per_s": round(1024 / sec4, 1), "ms_per_64_frame_batch": round(sec4 / 16 * 1e3, 3),
                                 "row_blocks_last_batch": int(cnt4.cpu().numpy()[0])}
-        del model4, frames4, ws4
+        del model4, ws4
+        # the lagged loop (Fig. 3b): the same model with the paper's placement (adapters on the last 20 % of the layers), a base
+        # head over the 80 labels on the shared layers' output, Alg. 2 on the previous frame's scores and the adapted layers, one
+        # call per 64 frames of the stream; nothing comes back to the host between the steps
+        model6 = binding.DeviceModel(cfg, w, L0=10)
+        bw6, bb6 = synth.make_base_head(cfg, K_labels, 78, bias_mean=-5.0)
+        s6 = binding.DeviceStream(model6, bw6, bb6, mem_np)
+        cap6 = 4 * 64
+        off6 = torch.zeros(65, dtype=torch.int32, device=dev)
+        ids6 = torch.zeros(cap6, dtype=torch.int32, device=dev)
+        cnt6 = torch.zeros(2, dtype=torch.int32, device=dev)
+        out6 = torch.zeros(cap6, cfg.C, device=dev)
+        base6 = torch.zeros(64, K_labels, device=dev)
+        merged6 = torch.zeros(64, K_labels, device=dev)
+        ws6 = torch.empty(binding.poly_stream_step_workspace_bytes(model6, 64, cap6, K_labels), dtype=torch.uint8, device=dev)
+
+        def loop_pass():
+            for _ in range(16):
+                binding.poly_stream_step(model6, s6, frames4, cap6, off6, ids6, cnt6, out6, ws6, out_base_scores=base6, out_merged=merged6)
+        sec6 = timed(loop_pass, 5, 2)
+        extra["lagged_loop_L0_10"] = {"frames_per_s": round(1024 / sec6, 1), "ms_per_64_frame_call": round(sec6 / 16 * 1e3, 3),
+                                      "row_blocks_last_call": int(cnt6.cpu().numpy()[0])}
+        del model6, frames4, ws6
         # config 3: ViT-base, 64 frames, adapters on qkv, proj, fc1 and fc2 (forward alone; its adapter sets are given)
         cfg3, w3, frames3_np, off3_np, ids3_np = synth.make_forward_case(3)
         model3 = binding.DeviceModel(cfg3, w3, L0=0)

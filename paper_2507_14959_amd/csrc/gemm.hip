@@ -636,6 +636,10 @@ static int launch_gemm_dma(const GemmArgs &g, hipStream_t st)
         launch_dma<256, 128, 4, 2, 2>(g, st);
     } else if (g.N % 128 == 0 || g.N >= 1024) {
         launch_dma<128, 128, 2, 2, 2>(g, st);
+    } else if ((long)g.n_in * ((g.T + 127) / 128) * ((g.N + 63) / 64) < 256) {
+        // fewer 128 x 64 tiles than CUs (the patch embedding of a small batch): half the rows per tile, twice the workgroups,
+        // two of them per CU
+        launch_dma<64, 64, 2, 2, 4>(g, st);
     } else {
         launch_dma<128, 64, 2, 2, 2>(g, st);
     }

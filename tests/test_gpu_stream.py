@@ -133,3 +133,27 @@ def test_stream_step_over_capacity_reports_and_writes_no_rows():
     got = run_calls(cfg, w, bw, bb, mem, [frames], L0=1, R_cap=5, K=K)[0]
     assert got["counters"][0] == 5 * n_ad and got["status"] != 0
     assert np.all(got["scores"] == 0)
+
+
+def test_stream_step_refuses_bad_arguments_on_the_host():
+    n_ad, gsz = 4, 3
+    K = n_ad * gsz
+    cfg, w, _, _, _ = synth.make_small_case(321, dtype=synth.DT_F32, targets=3, L=2, F=1, r=4, n_adapters=n_ad, hw=32, patch=8, C=gsz)
+    model = binding.DeviceModel(cfg, w, L0=1)
+    bw, bb = synth.make_base_head(cfg, K, 9)
+    dev = "cuda"
+    frames = model.frames_to_device(synth.make_frames(cfg, 2, np.random.default_rng(1)))
+    off = torch.zeros(3, dtype=torch.int32, device=dev)
+    ids = torch.zeros(8, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(2, dtype=torch.int32, device=dev)
+    scores = torch.zeros(8, cfg.C, device=dev)
+    need = binding.poly_stream_step_workspace_bytes(model, 2, 8, K)
+    assert need > binding.poly_forward_workspace_bytes(model, 2, 8)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    s = binding.DeviceStream(model, bw, bb, synth.make_group_membership(n_ad, gsz))
+    assert binding.poly_stream_step(model, s, frames, 8, off, ids, cnt, scores, ws[:need - 256], check=False) == binding.POLY_ECAP
+    # more contexts than the model has adapters: a context id would name an adapter that does not exist
+    wide = binding.DeviceStream(model, bw, bb, synth.make_group_membership(n_ad + 2, 2))
+    assert binding.poly_stream_step(model, wide, frames, 8, off, ids, cnt, scores, ws, check=False) == binding.POLY_EINVAL
+    s.c.carry = None
+    assert binding.poly_stream_step(model, s, frames, 8, off, ids, cnt, scores, ws, check=False) == binding.POLY_EINVAL

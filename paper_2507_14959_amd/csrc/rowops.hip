@@ -407,7 +407,7 @@ static void launch_head_t(int nx, dim3 grid, hipStream_t st, const float *x, con
 
 // ------------------------------------------------------------------ base head of the lagged loop
 // Block f: LayerNorm of frame f's class token (row 0 of its block of x) and the K label scores
-// sigmoid(z Wb[c] + bb[c]); wave w takes classes w, w + 4, ...  The scores go to lag[f + 1] (the selection of frame
+// sigmoid(z Wb[c] + bb[c]).  The scores go to lag[f + 1] (the selection of frame
 // f + 1 reads them there) and to out[f]; block 0 also copies the carried scores of the previous call to lag[0].
 template <typename T>
 __global__ __launch_bounds__(256) void base_head_kernel(const float *x, int T_tok, int D, const float *gain, const float *shift, float eps,
@@ -433,13 +433,26 @@ __global__ __launch_bounds__(256) void base_head_kernel(const float *x, int T_to
     const float inv = rsqrtf((part[4] + part[5] + part[6] + part[7]) / D + eps);
     for (int i = tid; i < D; i += 256) z[i] = (xr[i] - mean) * inv * gain[i] + shift[i];
     __syncthreads();
-    for (int c = wave; c < K; c += 4) {
-        const T *wr = Wb + (size_t)c * D;
-        float d = 0.f;
-        for (int i = lane; i < D; i += 64) d = fmaf(z[i], (float)wr[i], d);
-        d = wave_sum(d);
-        if (lane == 0) {
-            const float sc = 1.0f / (1.0f + expf(-(d + bb[c])));
+    // eight classes per wave and round: their weight loads are in flight together (one class at a time pays a memory
+    // round trip per class), and lane u finishes class c0 + u
+    for (int c0 = wave * 8; c0 < K; c0 += 32) {
+        float d[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) d[u] = 0.f;
+        for (int i = lane; i < D; i += 64) {
+            const float zi = z[i];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) d[u] = fmaf(zi, (float)Wb[(size_t)min(c0 + u, K - 1) * D + i], d[u]);
+        }
+        float mine = 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float t = wave_sum(d[u]);
+            if (lane == u) mine = t;
+        }
+        const int c = c0 + lane;
+        if (lane < 8 && c < K) {
+            const float sc = 1.0f / (1.0f + expf(-(mine + bb[c])));
             lag[(size_t)(f + 1) * K + c] = sc;
             if (out) out[(size_t)f * K + c] = sc;
         }

@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float *scores, int F,
     __shared__ int unc[CH];
     __shared__ uint64_t prevY[KWMAX], prevProv[KWMAX];
     __shared__ uint64_t prevS;
-    __shared__ int prevValid, total, total_unc;
+    __shared__ int prevValid, total, total_unc, lead_s;
     __shared__ int wtot[4], wunc[4];           // per wave: selected contexts, uncovered labels (scan below)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -160,8 +160,24 @@ __global__ __launch_bounds__(256) void select_kernel(const float *scores, int F,
             else greedy(std::integral_constant<int, KWMAX>{});
         }
         __syncthreads();
-        // reuse branches of Alg. 2, in frame order
-        if (sequential && tid == 0) {
+        // Reuse branches of Alg. 2.  Without context_copy a reused set is the greedy set of the same labels, so only the
+        // frames at the head of the call that repeat the carried labels take something else than their own greedy set
+        // (the carried one): found in parallel.  With context_copy a kept set need not be greedy: frame order.
+        if (sequential && context_copy == 0) {
+            if (tid == 0) lead_s = n;
+            __syncthreads();
+            if (tid < n) {
+                bool eq = true;
+                for (int j = 0; j < KW; ++j) eq &= Y[tid][j] == (tid ? Y[tid - 1][j] : prevY[j]);
+                if (!eq) atomicMin(&lead_s, tid);
+            }
+            __syncthreads();
+            const int lead = prevValid ? lead_s : 0;     // frames [0, lead) repeat the carried labels
+            if (tid < lead) S[tid] = prevS;
+            __syncthreads();
+            if (tid == 0) { prevS = S[n - 1]; prevValid = 1; }
+            if (tid < KW) prevY[tid] = Y[n - 1][tid];
+        } else if (sequential && tid == 0) {
             for (int t = 0; t < n; ++t) {
                 bool same = prevValid != 0, covered = prevValid != 0 && context_copy != 0;
                 for (int j = 0; j < KW; ++j) {

@@ -459,10 +459,90 @@ __global__ __launch_bounds__(256) void base_head_kernel(const float *x, int T_to
     }
 }
 
+// D = 64 ND: no LDS and no workgroup barrier -- every wave normalises the row for itself (lane l holds elements l + 64 j,
+// the layout its dot products need), and the weights of the next eight classes are requested before the sums of the
+// current eight are reduced, so that a round costs one memory round trip instead of one per K step
+template <typename T, int ND>
+__global__ __launch_bounds__(256) void base_head_nd_kernel(const float *x, int T_tok, const float *gain, const float *shift, float eps,
+                                                           const T *Wb, const float *bb, int K, float *lag, float *out, const float *carry)
+{
+    constexpr int D = 64 * ND, CW = 8;
+    const int f = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float *xr = x + (size_t)f * T_tok * D;
+    float xv[ND], g[ND], sh[ND];
+#pragma unroll
+    for (int j = 0; j < ND; ++j) { xv[j] = xr[lane + 64 * j]; g[j] = gain[lane + 64 * j]; sh[j] = shift[lane + 64 * j]; }
+    auto loadw = [&](T(&w)[CW][ND], int c0) {
+#pragma unroll
+        for (int u = 0; u < CW; ++u)
+#pragma unroll
+            for (int j = 0; j < ND; ++j) w[u][j] = Wb[(size_t)min(c0 + u, K - 1) * D + lane + 64 * j];
+    };
+    T w0[CW][ND];
+    loadw(w0, wave * CW);
+    if (f == 0)
+        for (int c = tid; c < K; c += 256) lag[c] = carry ? carry[c] : 0.f;
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < ND; ++j) s += xv[j];
+    const float mean = wave_sum(s) / D;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < ND; ++j) { const float d = xv[j] - mean; q += d * d; }
+    const float inv = rsqrtf(wave_sum(q) / D + eps);
+    float z[ND];
+#pragma unroll
+    for (int j = 0; j < ND; ++j) z[j] = (xv[j] - mean) * inv * g[j] + sh[j];
+    for (int c0 = wave * CW; c0 < K; c0 += 4 * CW) {
+        T w1[CW][ND];
+        const bool more = c0 + 4 * CW < K;          // uniform
+        if (more) loadw(w1, c0 + 4 * CW);
+        float mine = 0.f;
+#pragma unroll
+        for (int u = 0; u < CW; ++u) {
+            float d = 0.f;
+#pragma unroll
+            for (int j = 0; j < ND; ++j) d = fmaf(z[j], (float)w0[u][j], d);
+            d = wave_sum(d);
+            if (lane == u) mine = d;
+        }
+        const int c = c0 + lane;
+        if (lane < CW && c < K) {
+            const float sc = 1.0f / (1.0f + expf(-(mine + bb[c])));
+            lag[(size_t)(f + 1) * K + c] = sc;
+            if (out) out[(size_t)f * K + c] = sc;
+        }
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < CW; ++u)
+#pragma unroll
+                for (int j = 0; j < ND; ++j) w0[u][j] = w1[u][j];
+        }
+    }
+}
+
+template <typename T>
+static bool launch_base_head_nd(int D, int F, hipStream_t st, const float *x, int T_tok, const float *gain, const float *shift, float eps,
+                                const T *Wb, const float *bb, int K, float *lag, float *out, const float *carry)
+{
+    switch (D) {
+#define POLY_BH_CASE(ND)                                                                                                            \
+    case 64 * ND:                                                                                                                   \
+        POLY_LAUNCH(POLY_STAGE_OTHER, (base_head_nd_kernel<T, ND>), dim3(F), dim3(256), st, x, T_tok, gain, shift, eps, Wb, bb, K, lag, out, carry); \
+        return true;
+        POLY_BH_CASE(1) POLY_BH_CASE(2) POLY_BH_CASE(3) POLY_BH_CASE(4) POLY_BH_CASE(6) POLY_BH_CASE(8) POLY_BH_CASE(12)
+#undef POLY_BH_CASE
+    default: return false;
+    }
+}
+
 int launch_base_head(const float *x, int T, int D, const float *gain, const float *shift, float eps, const void *Wb, const float *bb,
                      int K, int F, float *lag, float *out, const float *carry, int dtype, hipStream_t st)
 {
     if (F == 0) return POLY_OK;
+    if (dtype == POLY_BF16 ? launch_base_head_nd<bf16_t>(D, F, st, x, T, gain, shift, eps, (const bf16_t *)Wb, bb, K, lag, out, carry)
+                           : launch_base_head_nd<float>(D, F, st, x, T, gain, shift, eps, (const float *)Wb, bb, K, lag, out, carry))
+        return hip_ok();
     const size_t lds = sizeof(float) * (size_t)(D + 8);
     if (dtype == POLY_BF16)
         POLY_LAUNCH_SHMEM(POLY_STAGE_OTHER, base_head_kernel<bf16_t>, dim3(F), dim3(256), lds, st, x, T, D, gain, shift, eps, (const bf16_t *)Wb, bb,

@@ -90,7 +90,8 @@ def test_stream_step_fp32_matches_checker_exactly(L0, seed):
     assert check_stream(synth.DT_F32, seed, L0) > 0
 
 
-@pytest.mark.parametrize("seed,L0,D,heads,Dm", [(310, 2, 192, 3, 384), (311, 1, 256, 4, 512)])
+@pytest.mark.parametrize("seed,L0,D,heads,Dm", [(310, 2, 192, 3, 384), (311, 1, 256, 4, 512),
+                                                  (312, 1, 320, 5, 640)])     # D = 320: the base head kernel for any width
 def test_stream_step_bf16(seed, L0, D, heads, Dm):
     check_stream(synth.DT_BF16, seed, L0, D=D, heads=heads, Dm=Dm, exact=False)
 

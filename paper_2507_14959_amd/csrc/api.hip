@@ -376,17 +376,11 @@ extern "C" size_t poly_lora_linear_workspace_bytes(int n_xblocks, int T, int r, 
     return carve_linear(T, r, R, dtype, nullptr).bytes;
 }
 
-extern "C" int poly_lora_linear(const void *X, int n_xblocks, int T, int Kdim, const void *Wt, const float *bias, int Ndim,
-                                const void *At, const void *Bt, int n_adapters, int r, float scale, const int32_t *row_offsets,
-                                const int32_t *adapter_ids, int R, void *Y, int dtype, int32_t *dev_status, void *workspace,
-                                size_t workspace_bytes, void *stream)
+namespace {
+int lora_linear_impl(const void *X, int n_xblocks, int T, int Kdim, const void *Wt, const float *bias, int Ndim, const void *At,
+                     const void *Bt, int n_adapters, int r, float scale, const int32_t *row_offsets, const int32_t *adapter_ids, int R,
+                     void *Y, int dtype, int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (dtype != POLY_F32 && dtype != POLY_BF16) return POLY_EINVAL;
-    if (n_xblocks < 0 || T <= 0 || Kdim <= 0 || Ndim <= 0 || n_adapters <= 0 || r <= 0 || r > POLY_MAX_RANK || R < 0) return POLY_EINVAL;
-    if (Kdim % (dtype == POLY_BF16 ? 8 : 4)) return POLY_EINVAL;
-    if (n_xblocks == 0) return POLY_OK;
-    if (!X || !Wt || !At || !Bt || !row_offsets || (R > 0 && (!adapter_ids || !Y))) return POLY_EINVAL;
-    if (!workspace || ((uintptr_t)workspace & 255) != 0) return POLY_EINVAL;
     const LinearWs w = carve_linear(T, r, R, dtype, workspace);
     if (workspace_bytes < w.bytes) return POLY_ECAP;
     hipStream_t st = (hipStream_t)stream;
@@ -401,4 +395,28 @@ extern "C" int poly_lora_linear(const void *X, int n_xblocks, int T, int Kdim, c
     g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = r; g.adapter_of_out = w.adapter_of_row;
     g.mode = EPI_STORE; g.out = Y; g.Tout = T;
     return launch_gemm(g, dtype, st);
+}
+
+int check_lora_linear(const void *X, int n_xblocks, int T, int Kdim, const void *Wt, int Ndim, const void *At, const void *Bt,
+                      int n_adapters, int r, const int32_t *row_offsets, const int32_t *adapter_ids, int R, void *Y, int dtype)
+{
+    if (dtype != POLY_F32 && dtype != POLY_BF16) return POLY_EINVAL;
+    if (n_xblocks < 0 || T <= 0 || Kdim <= 0 || Ndim <= 0 || n_adapters <= 0 || r <= 0 || r > POLY_MAX_RANK || R < 0) return POLY_EINVAL;
+    if (Kdim % (dtype == POLY_BF16 ? 8 : 4)) return POLY_EINVAL;
+    if (n_xblocks == 0) return POLY_OK;
+    if (!X || !Wt || !At || !Bt || !row_offsets || (R > 0 && (!adapter_ids || !Y))) return POLY_EINVAL;
+    return POLY_OK;
+}
+}  // namespace
+
+extern "C" int poly_lora_linear(const void *X, int n_xblocks, int T, int Kdim, const void *Wt, const float *bias, int Ndim,
+                                const void *At, const void *Bt, int n_adapters, int r, float scale, const int32_t *row_offsets,
+                                const int32_t *adapter_ids, int R, void *Y, int dtype, int32_t *dev_status, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    POLY_TRY(check_lora_linear(X, n_xblocks, T, Kdim, Wt, Ndim, At, Bt, n_adapters, r, row_offsets, adapter_ids, R, Y, dtype));
+    if (n_xblocks == 0) return POLY_OK;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0) return POLY_EINVAL;
+    return lora_linear_impl(X, n_xblocks, T, Kdim, Wt, bias, Ndim, At, Bt, n_adapters, r, scale, row_offsets, adapter_ids, R, Y, dtype,
+                            dev_status, workspace, workspace_bytes, stream);
 }

@@ -76,10 +76,25 @@ def test_base_product_is_shared_by_row_blocks_of_one_input():
     assert np.array_equal(Y[0], Y[1]) and not np.array_equal(Y[0], Y[2])
 
 
-def test_config5_full_size_on_sampled_row_blocks():
-    case = synth.make_lora_linear_case()                 # 256 x 197 x 768 -> 2304, 64 adapters of rank 16, R = 512
+def test_config5_full_size_every_row_block():
+    """256 x 197 x 768 -> 2304, 64 adapters of rank 16, R = 512: the 256 x 256 tiles that run across block boundaries, the
+    eight per-XCD runs and the fan-out of every X block into two row-blocks, all 512 row-blocks element by element."""
+    case = synth.make_lora_linear_case()
     Y, st = gpu_lora_linear(case)
     assert st == 0 and Y.shape == (512, 197, 2304)
-    for b in (0, 1, 255, 300, 511):
-        check(Y[b:b + 1], oracle.lora_linear(case, b_begin=b, b_end=b + 1), synth.DT_BF16)
-    assert np.isfinite(Y).all()
+    worst = 0.0
+    for b in range(0, 512, 32):                          # the checker in chunks of 32 row-blocks (116 MB of doubles each)
+        want = oracle.lora_linear(case, b_begin=b, b_end=b + 32)
+        check(Y[b:b + 32], want, synth.DT_BF16)
+        worst = max(worst, float(np.abs(Y[b:b + 32] - want).max()))
+    print(f"config 5: max-abs error over all 512 row-blocks {worst:.2e}")
+
+
+def test_deep_layer_shape_no_shared_inputs_full_compare():
+    """No two row-blocks share an input (one adapter per X block) and a block count that leaves the last 256-row tile ragged:
+    600 blocks of 197 rows are 462 tiles (118 200 = 461 * 256 + 184), enough for the big tiles (>= 512 with three column tiles)."""
+    case = synth.make_lora_linear_case(n_xblocks=600, T=197, Kdim=512, Ndim=768, n_adapters=9, r=16, per_block=1, seed=77)
+    Y, st = gpu_lora_linear(case, scale=0.5)
+    assert st == 0
+    for b in range(0, 600, 100):
+        check(Y[b:b + 100], oracle.lora_linear(case, s=0.5, b_begin=b, b_end=b + 100), synth.DT_BF16)

@@ -67,6 +67,40 @@ def test_overlapping_contexts_with_accuracy_table_and_state(seed, copy):
         assert np.array_equal(ids, o_ids) and unc == o_unc
 
 
+@pytest.mark.parametrize("copy", [False, True])
+@pytest.mark.parametrize("K,M", [(80, 45), (200, 64)])
+def test_reuse_branches_across_passes_of_one_call(K, M, copy):
+    """300 frames of a sticky stream in ONE call with a carried state: the call spans three passes of 128 frames, so the previous
+    labels, set and provenance are handed from pass to pass (and, with context_copy, the sequential loop runs in every pass)."""
+    rng = np.random.default_rng(900 + K)
+    mem, acc = synth.make_cover_instance(K, K, M, max_size=6, with_acc=True)
+    T = 300
+    Y, cur = np.zeros((T, K), dtype=bool), np.zeros(K, dtype=bool)
+    for t in range(T):
+        if rng.random() < 0.3:
+            cur = cur.copy()
+            if cur.any() and rng.random() < 0.5:
+                cur[rng.choice(np.flatnonzero(cur))] = False              # a label leaves: context_copy keeps the old set
+            else:
+                cur[rng.choice(K, size=int(rng.integers(1, 3)), replace=False)] = True
+            if cur.sum() > 4:
+                cur = np.zeros(K, dtype=bool)
+        Y[t] = cur
+    scores = np.where(Y, 0.9, 0.1).astype(np.float32)
+    o_state = oracle.SelectState(K, M)
+    g_state = torch.zeros(binding.poly_select_state_bytes(K), dtype=torch.uint8, device="cuda")
+    # a short first call so that the long one starts from a non-trivial state
+    for a, b in ((0, 9), (9, T)):
+        o_off, o_ids, o_unc = oracle.select(scores[a:b], mem, acc=acc, tau=0.3, context_copy=copy, state=o_state)
+        off, ids, n, unc = gpu_select(scores[a:b], mem, acc=acc, tau=0.3, context_copy=copy, state=g_state)
+        assert np.array_equal(off, o_off) and np.array_equal(ids, o_ids) and unc == o_unc and n == len(o_ids)
+    if copy:
+        # the copy branch must have made a difference somewhere, or the case does not exercise it
+        p_off, p_ids, _ = oracle.select(scores, mem, acc=acc, tau=0.3, context_copy=False, state=oracle.SelectState(K, M))
+        c_off, c_ids, _ = oracle.select(scores, mem, acc=acc, tau=0.3, context_copy=True, state=oracle.SelectState(K, M))
+        assert not (np.array_equal(p_off, c_off) and np.array_equal(p_ids, c_ids))
+
+
 def test_threshold_is_inclusive_and_empty_frames_give_empty_sets():
     mem = synth.make_group_membership(4, 5)
     s = np.zeros((3, 20), dtype=np.float32)

@@ -90,10 +90,11 @@ def test_stream_step_fp32_matches_checker_exactly(L0, seed):
     assert check_stream(synth.DT_F32, seed, L0) > 0
 
 
-@pytest.mark.parametrize("seed,L0,D,heads,Dm", [(310, 2, 192, 3, 384), (311, 1, 256, 4, 512),
-                                                  (312, 1, 320, 5, 640)])     # D = 320: the base head kernel for any width
+# seeds whose scores (from the checker) all keep > 4e-2 from theta and whose active label set changes within the 12 frames, so every
+# frame's adapter set, logits and merged scores are compared; D = 320: the base head kernel for any width
+@pytest.mark.parametrize("seed,L0,D,heads,Dm", [(581, 2, 192, 3, 384), (683, 1, 256, 4, 512), (751, 1, 320, 5, 640)])
 def test_stream_step_bf16(seed, L0, D, heads, Dm):
-    check_stream(synth.DT_BF16, seed, L0, D=D, heads=heads, Dm=Dm, exact=False)
+    assert check_stream(synth.DT_BF16, seed, L0, D=D, heads=heads, Dm=Dm, exact=True) > 0
 
 
 def test_stream_step_deit_tiny_placement_of_the_paper():

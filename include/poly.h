@@ -234,6 +234,26 @@ int poly_lora_linear(const void *X, int n_xblocks, int T, int Kdim, const void *
                      int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * poly_lora_linear_static -- poly_lora_linear for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels and same results, but
+ * the scratch memory (bookkeeping words, row maps, shrink output S) is a device array of POLY_STATIC_SCRATCH_BYTES
+ * bytes inside the library instead of a workspace argument.  Every GPU the library runs on holds that array until the
+ * process ends.  The call allocates and frees nothing; the first call on a device looks up the array's address on that
+ * device (make that first call outside a graph capture).
+ *   Limit: poly_lora_linear_workspace_bytes(n_xblocks, T, r, R, dtype) <= POLY_STATIC_SCRATCH_BYTES, else POLY_ECAP
+ *   and nothing is launched (bf16, T = 197, r <= 16: R <= 664 row-blocks).
+ *   All calls on one GPU share the one array: calls that overlap in time on the same GPU (different streams or
+ *   threads) race on it; calls on one stream are ordered and safe.  The array keeps the last call's contents; nothing
+ *   in it needs clearing between calls.
+ */
+enum { POLY_STATIC_SCRATCH_BYTES = 4 * 1024 * 1024 };
+
+int poly_lora_linear_static(const void *X, int n_xblocks, int T, int Kdim, const void *Wt, const float *bias,
+                            int Ndim, const void *At, const void *Bt, int n_adapters, int r, float scale,
+                            const int32_t *row_offsets, const int32_t *adapter_ids, int R, void *Y, int dtype,
+                            int32_t *dev_status, void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * Per-stage kernel timing for measurement harnesses (not part of the method).  Between
  * poly_profile_begin and poly_profile_end every kernel the library launches carries a start/stop
  * event pair stamped by the runtime with the dispatch's own begin and end, and poly_profile_end

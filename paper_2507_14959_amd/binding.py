@@ -22,7 +22,8 @@ LIB_PATH = os.path.join(_HERE, "libpoly.so")
 
 EXPORTS = ("poly_status_string", "poly_select_state_bytes", "poly_select", "poly_forward_workspace_bytes",
            "poly_forward", "poly_stream_step_workspace_bytes", "poly_stream_step", "poly_lora_linear_workspace_bytes",
-           "poly_lora_linear", "poly_profile_begin", "poly_profile_end")
+           "poly_lora_linear", "poly_lora_linear_static", "poly_profile_begin", "poly_profile_end")
+STATIC_SCRATCH_BYTES = 4 * 1024 * 1024
 STAGES = ("select", "gemm", "shrink", "attention", "layernorm", "other")
 
 
@@ -96,6 +97,8 @@ def lib():
         L.poly_lora_linear.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                        C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p, C.c_void_p,
                                        C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.poly_lora_linear_static.restype = C.c_int
+        L.poly_lora_linear_static.argtypes = L.poly_lora_linear.argtypes[:18] + [C.c_void_p]
         L.poly_profile_begin.restype = C.c_int
         L.poly_profile_begin.argtypes = [C.c_int]
         L.poly_profile_end.restype = C.c_int
@@ -273,6 +276,22 @@ def poly_lora_linear(X: torch.Tensor, Wt: torch.Tensor, bias: Optional[torch.Ten
                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     if check and rc != POLY_OK:
         raise PolyError(rc, "poly_lora_linear")
+    return rc
+
+
+def poly_lora_linear_static(X: torch.Tensor, Wt: torch.Tensor, bias: Optional[torch.Tensor], At: torch.Tensor, Bt: torch.Tensor,
+                            scale: float, row_offsets: torch.Tensor, adapter_ids: torch.Tensor, R: int, Y: torch.Tensor,
+                            dev_status: Optional[torch.Tensor] = None, stream=None, check: bool = True) -> int:
+    """poly_lora_linear on the library's own static scratch array: no workspace argument, nothing allocated."""
+    n_xblocks, T, Kdim = X.shape
+    Ndim = Wt.shape[0]
+    n_adapters, r = At.shape[0], At.shape[1]
+    dtype = POLY_BF16 if X.dtype == torch.bfloat16 else POLY_F32
+    rc = lib().poly_lora_linear_static(_ptr(X), n_xblocks, T, Kdim, _ptr(Wt), _ptr(bias), Ndim, _ptr(At), _ptr(Bt), n_adapters, r,
+                                       scale, _ptr(row_offsets), _ptr(adapter_ids), R, _ptr(Y), dtype, _ptr(dev_status),
+                                       _stream(stream))
+    if check and rc != POLY_OK:
+        raise PolyError(rc, "poly_lora_linear_static")
     return rc
 
 

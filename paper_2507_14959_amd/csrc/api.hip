@@ -420,3 +420,43 @@ extern "C" int poly_lora_linear(const void *X, int n_xblocks, int T, int Kdim, c
     return lora_linear_impl(X, n_xblocks, T, Kdim, Wt, bias, Ndim, At, Bt, n_adapters, r, scale, row_offsets, adapter_ids, R, Y, dtype,
                             dev_status, workspace, workspace_bytes, stream);
 }
+
+// ------------------------------------------------------------------ isolated linear without a caller workspace
+// For callers that cannot allocate (code under graph capture, serving loops, harnesses that forbid hipMalloc): the bookkeeping,
+// the row maps and the shrink output S live in a file-scope device array instead of a workspace argument.  Each GPU the library
+// is loaded on holds its own copy of the array; its address on a device is looked up once, with that device current.
+static __device__ __align__(256) unsigned char scratch[POLY_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void *scratch_of_device[MAX_DEVICES];          // device address of `scratch` per device ordinal, null until looked up
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return POLY_EHIP;
+    void *p = __atomic_load_n(&scratch_of_device[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return POLY_EHIP;
+        __atomic_store_n(&scratch_of_device[dev], p, __ATOMIC_RELEASE);   // (two racing first calls look up the same address)
+    }
+    *out = p;
+    return POLY_OK;
+}
+}  // namespace
+
+extern "C" int poly_lora_linear_static(const void *X, int n_xblocks, int T, int Kdim, const void *Wt, const float *bias, int Ndim,
+                                       const void *At, const void *Bt, int n_adapters, int r, float scale,
+                                       const int32_t *row_offsets, const int32_t *adapter_ids, int R, void *Y, int dtype,
+                                       int32_t *dev_status, void *stream)
+{
+    POLY_TRY(check_lora_linear(X, n_xblocks, T, Kdim, Wt, Ndim, At, Bt, n_adapters, r, row_offsets, adapter_ids, R, Y, dtype));
+    if (n_xblocks == 0) return POLY_OK;
+    if (carve_linear(T, r, R, dtype, nullptr).bytes > (size_t)POLY_STATIC_SCRATCH_BYTES) return POLY_ECAP;
+    void *ws = nullptr;
+    POLY_TRY(static_scratch(&ws));
+    // nothing in the scratch area has to start at zero: the CSR check writes the bookkeeping words and the row maps of every
+    // row it accepts, and the shrink writes all RP columns of every S row the product reads
+    return lora_linear_impl(X, n_xblocks, T, Kdim, Wt, bias, Ndim, At, Bt, n_adapters, r, scale, row_offsets, adapter_ids, R, Y, dtype,
+                            dev_status, ws, POLY_STATIC_SCRATCH_BYTES, stream);
+}

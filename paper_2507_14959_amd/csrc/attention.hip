@@ -12,12 +12,6 @@ namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
 
-// phase timestamps for tuning; a test harness defines the macros before including this file
-#ifndef AT_TS
-#define AT_TS(i)
-#define AT_TS_END
-#endif
-
 template <int NKT>  // 32-key tiles: T <= 32 * NKT
 __global__ __launch_bounds__(512) void attn_bf16_kernel(const bf16_t *qkv, bf16_t *out, int T, int D, int heads, int n_blocks,
                                                         const int *n_blocks_dev)
@@ -31,7 +25,6 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(const bf16_t *qkv, bf16_
     bf16_t *Vt = Ks + TKP * KS;              // [64][VS]
     bf16_t *Ot = Vt + 64 * VS;               // [waves][32][OS]: finished outputs of a wave's query tile, for row-wise stores
 
-    AT_TS(0);
     const int nb = n_blocks_dev ? min(*n_blocks_dev, n_blocks) : n_blocks;
     const int b = blockIdx.x / heads, hd = blockIdx.x % heads;
     if (b >= nb) return;
@@ -39,7 +32,6 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(const bf16_t *qkv, bf16_
     const size_t ld = (size_t)3 * D;
     const bf16_t *base = qkv + (size_t)b * T * ld + hd * 64;
     const int nthreads = blockDim.x;
-    AT_TS(1);
 
     // everything this thread will read from global memory is requested up front: its queries (wave w owns the 32-query
     // tile w), then its share of K (16-byte pieces) and of V (an 8 keys x 8 columns block, transposed in registers below).
@@ -75,9 +67,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(const bf16_t *qkv, bf16_
         const int v = tid + i * nthreads;
         if (v < TKP * 8) *(bf16x8 *)(Ks + (v >> 3) * KS + (v & 7) * 8) = kp[i];
     }
-    AT_TS(2);
     __syncthreads();
-    AT_TS(3);
 
     {
         // S^T tile kt: rows = keys kt*32 + 8*(e/4) + 4*lh + e%4, column = this lane's query.  The K fragments of tile
@@ -100,7 +90,6 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(const bf16_t *qkv, bf16_
             __builtin_amdgcn_sched_barrier(0);
         }
 
-        AT_TS(4);
         // only the last key tile can hold keys past T (T > 32 * (NKT - 1) by construction)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -131,7 +120,6 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(const bf16_t *qkv, bf16_
                 }
         sum += __shfl_xor(sum, 32, 64);
 
-        AT_TS(5);
         // O^T = V^T P^T: rows = head columns, column = this lane's query; V^T fragments one step ahead as above
         f32x16 o[2];
 #pragma unroll
@@ -163,7 +151,6 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(const bf16_t *qkv, bf16_
             __builtin_amdgcn_sched_barrier(0);
         }
 
-        AT_TS(6);
         // a lane owns one query: stored from registers, every instruction would touch 32 cache lines with 8 bytes each.
         // The wave lays its 32 x 64 tile out in LDS and stores 16-byte pieces, 8 lanes per row
         const float inv = 1.0f / sum;
@@ -184,9 +171,7 @@ __global__ __launch_bounds__(512) void attn_bf16_kernel(const bf16_t *qkv, bf16_
             const bf16x8 v = *(const bf16x8 *)(ot + row * OS + (lane & 7) * 8);
             if (qrow < T) *(bf16x8 *)(out + ((size_t)b * T + qrow) * D + hd * 64 + (lane & 7) * 8) = v;
         }
-        AT_TS(7);
     }
-    AT_TS_END;
 }
 
 // fp32 path: keys and values go through LDS in chunks of 64; each thread keeps q, the running

@@ -9,13 +9,6 @@
 
 #include <stdlib.h>
 
-// phase timestamps for tuning; a test harness defines the macros before including this file
-#ifndef GM_TS
-#define GM_TS(i)
-#define GM_TS_END
-#define GM_TS_BYTES 0
-#endif
-
 namespace {
 
 template <typename T> __device__ __forceinline__ void epilogue_store_elt(const GemmArgs &g, int ob, int t, int col, float v)
@@ -261,7 +254,6 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
 
     int mt, tn;
     if (!xcd_tile(blockIdx.x, g.n_in * tiles_m, tiles_n, PANEL, mt, tn)) return;
-    GM_TS(0);
     const int xb = mt / tiles_m, t0 = (mt - xb * tiles_m) * BM, n0 = tn * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -307,7 +299,6 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
         return;
     }
 
-    GM_TS(1);
     f32x16 acc[MI][NJ];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -386,9 +377,7 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
                 for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
         }
     }
-    GM_TS(2);
     __syncthreads();   // all loads have landed (vmcnt(0) above) and all waves are done with the tiles
-    GM_TS(3);
 
     // ---- epilogue, wave by wave and 32 rows at a time: no workgroup barrier is needed because each wave stages
     // through its own LDS region and the LDS executes one wave's instructions in order.
@@ -482,10 +471,7 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
                 }
                 lo = hi;
             }
-            if (i == MI / 2 - 1) GM_TS(4);
         }
-        GM_TS(5);
-        GM_TS_END;
         return;
     }
 
@@ -529,9 +515,7 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
             }
             emit(c, ob, rb, tw, 0, min(32, g.T - tw));
         }
-        GM_TS(ob == ob0 ? 4 : 5);
     }
-    GM_TS_END;
 }
 
 // ------------------------------------------------------------------ fp32 vector ALU
@@ -610,7 +594,7 @@ static unsigned dma_grid(int tiles_mtot, int tiles_n)
 template <int BM, int BN, int WM, int WN, int NS>
 static void launch_dma(const GemmArgs &g, hipStream_t st)
 {
-    constexpr int LDS = NS * (BM + BN) * 64 * 2 + GM_TS_BYTES;
+    constexpr int LDS = NS * (BM + BN) * 64 * 2;
     auto kern = gemm_bf16_dma_kernel<BM, BN, WM, WN, NS>;
     if (LDS > 64 * 1024) {
         static bool attr_set = false;   // raising the dynamic LDS limit is a per-kernel, process-wide setting

@@ -23,13 +23,6 @@
 
 #include <type_traits>
 
-// phase timestamps for tuning; a test harness defines the macros before including this file
-#ifndef MLP_TS
-#define MLP_TS(i)
-#define MLP_TS_END
-#define MLP_TS_BYTES 0
-#endif
-
 namespace {
 
 constexpr int ML_NS = 5;           // LDS stages of the weight stream
@@ -62,7 +55,6 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
     //   q = 0, 1: W1(0), W1(1);   q = 2, 3: W2(0), W1(2);   q = 4, 5: W2(1), W1(3);  ...  ; last two: W2(nch-2), W2(nch-1).
     // Loader wave w loads rows 16w .. 16w + 15 of each of the item's KT tiles, 8 rows (1 KB) per load.  A row's
     // 128 bytes land in lane order; the tile swizzle is applied by permuting the 16-byte pieces on the global side.
-    MLP_TS(0);
     const int lw = wave & 3, lr = lane >> 3;
     auto issue_item = [&](int q) {
         const bool second = q >= 2 && ((q & 1) == 0 || q == NQ - 1);
@@ -98,14 +90,12 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
         b2v = a.b2[min(tid, D - 1)];
     }
 
-    MLP_TS(1);
     const long n_out = a.n_out_dev ? min(*a.n_out_dev, a.n_out) : a.n_out;
     const long nrows = n_out * a.T;
     if (t0 >= nrows) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         return;
     }
-    MLP_TS(2);
     const int rows = (int)min(64L, nrows - t0);
     // the weight stream (workgroups past the row count have left without moving data): only the items of steps 0 and 1
     // for now -- the x rows are still on their way and would be slowed down by more; the rest of the ring follows
@@ -130,9 +120,7 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
     } else {
         ln_finish<KT, 4>(xv, gb_s, a.eps, As, tid);
     }
-    MLP_TS(3);
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    MLP_TS(4);
 
     // LayerNorm(x) rows wr*32 + lm as the B operand of the first product
     bf16x8 fa[KT * 4];
@@ -172,9 +160,7 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
     // with a quarter of the GELU arithmetic between them".
     auto compute_step = [&](auto D1, auto DG, auto D2, int h) {
         constexpr bool d1 = decltype(D1)::value, dg = decltype(DG)::value, d2 = decltype(D2)::value;
-        MLP_TS(40 + h);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        MLP_TS(8 + h);
         const bf16_t *s2 = Ws + ((h == nch + 1 ? NQ - 1 : 2 * h - 2) % ML_NS) * IT_EL;   // W2(h - 2)
         const bf16_t *s1 = Ws + ((h < 2 ? h : 2 * h - 1) % ML_NS) * IT_EL;               // W1(h)
         const bf16_t *Hr = Hs + (h & 1) * 4096;                                          // chunk h - 2
@@ -234,7 +220,6 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
 #pragma unroll
             for (int e = 0; e < 16; ++e) hnext[e] = 0.f;
         }
-        MLP_TS(24 + h);
     };
     using T_ = std::true_type;
     using F_ = std::false_type;
@@ -252,7 +237,6 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
     // ---- y as a row-major fp32 tile [64][D] in LDS (the ring is dead: every item was waited for before the last
     // barrier), then all threads add b2 + x and store full rows
     constexpr int stride = D * 4 + 16;           // bytes; rows start 4 banks apart
-    MLP_TS(5);
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // every wave is done reading the ring and the hidden tiles
     if (!loader) {
         char *prow = (char *)lds + (wr * 32 + lm) * stride + (wc * 32 * KT) * 4 + 16 * lh;
@@ -263,7 +247,6 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
                 *(f32x4 *)(prow + (p * 32 + 8 * g4) * 4) = f32x4{y[p][4 * g4], y[p][4 * g4 + 1], y[p][4 * g4 + 2], y[p][4 * g4 + 3]};
     }
     __syncthreads();
-    MLP_TS(6);
     constexpr int pieces = D / 4;                // 16-byte pieces per row
     const char *P = (const char *)lds;
     for (int idx = tid; idx < rows * pieces; idx += ML_THREADS) {
@@ -272,13 +255,11 @@ __global__ __launch_bounds__(ML_THREADS) void mlp_kernel(const MlpArgs a)
         f32x4 *xp = (f32x4 *)(xt + (size_t)row * D + 4 * p);
         *xp = *xp + v;
     }
-    MLP_TS(7);
-    MLP_TS_END;
 }
 
 template <int KT> int launch_mlp_kt(const MlpArgs &a, hipStream_t st)
 {
-    constexpr int LDS = ((KT < 2 ? 2 : KT) + ML_NS * KT) * 64 * 64 * 2 + (ML_MAX_DM + 64 * KT + 64 + 128 * KT) * 4 + MLP_TS_BYTES;
+    constexpr int LDS = ((KT < 2 ? 2 : KT) + ML_NS * KT) * 64 * 64 * 2 + (ML_MAX_DM + 64 * KT + 64 + 128 * KT) * 4;
     auto kern = mlp_kernel<KT>;
     if (LDS > 64 * 1024) {
         static bool attr_set = false;   // raising the dynamic LDS limit is a per-kernel, process-wide setting

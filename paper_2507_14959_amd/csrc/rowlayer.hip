@@ -30,14 +30,6 @@
 
 #include <type_traits>
 
-// phase timestamps for tuning; a test harness defines the macros before including this file
-#ifndef LY_TS
-#define LY_TS(i)
-#define LY_TSS(slot)
-#define LY_TS_END
-#define LY_TS_BYTES 0
-#endif
-
 namespace {
 
 constexpr int LY_NS = 5;            // LDS stages of the weight stream
@@ -69,7 +61,6 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     // a region of its own (narrower models leave LDS to spare)
     float *gelu_s = KT == 3 ? (float *)(As + 2 * 4096) : (float *)(at_s + 16 * LY_AT_STRIDE);
 
-    LY_TS(0);
     const int tiles = (a.T + 63) / 64;
     const int ob = blockIdx.x / tiles, t0 = (blockIdx.x % tiles) * 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -163,7 +154,6 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         load_res(ob);
     }
 
-    LY_TS(1);
     const int n_out = a.n_out_dev ? min(*a.n_out_dev, a.n_out) : a.n_out;
     if (ob >= n_out) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -179,7 +169,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     auto refill = [&](int cpos, int cap) {
         while (last + 1 < NI && pos_of(last + 1) <= min(cpos + LY_NS, cap)) {
             ++last;
-            if (wave == 4) { issue_item(last); LY_TSS(128 + last); }
+            if (wave == 4) { issue_item(last); }
         }
     };
     // item `need` has landed; newer ones may stay in flight (loads complete in issue order; the counter holds 63).
@@ -192,7 +182,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     };
     auto issue_next = [&]() {                    // the next item, whatever its position (the caller knows its stage is free)
         ++last;
-        if (wave == 4) { issue_item(last); LY_TSS(128 + last); }
+        if (wave == 4) { issue_item(last); }
     };
 
     if (loader) {
@@ -224,9 +214,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             if (tid + 256 * j < Dm) b1_s[tid + 256 * j] = b1v[j];
         if (tid < D) b2_s[tid] = b2v;
     }
-    LY_TS(2);
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // B0: o rows, biases, gains are in LDS
-    LY_TS(3);
 
     const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     const bf16x4 zero4 = {0, 0, 0, 0};
@@ -357,12 +345,9 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
                 if (s == 0) issue_next();                                           // W1's first rows: stage 3 is free all through A
             }
             wait_item(NA - 1);                                                  // Bf: Bt_k has landed (it is older than the items still in flight)
-            LY_TS(5);
             asm volatile("s_barrier" ::: "memory");                             // Bs: the tile is complete
-            LY_TS(6);
             add_tile();
             ln_rows(gb2_s);
-            LY_TS(7);
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bl: LayerNorm2(x') is in As, the tile is dead
         } else {
             load_fa();
@@ -374,7 +359,6 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             }
             bf16x8 fs = zero8;
             if (lora_p) fs = shrink(a.r);                                       // At_k landed before the first chunk did
-            LY_TS(4);
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bf
             if (lora_p) {
 #pragma unroll
@@ -387,11 +371,8 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
 #pragma unroll
                 for (int g = 0; g < 4; ++g)
                     *(f32x4 *)(trow + (c * 64 + 8 * g) * 4) = f32x4{accp[c][4 * g], accp[c][4 * g + 1], accp[c][4 * g + 2], accp[c][4 * g + 3]};
-            LY_TS(5);
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // Bs
-            LY_TS(6);
             asm volatile("s_barrier" ::: "memory");                             // Bl
-            LY_TS(7);
         }
     } else {
         if (loader) {
@@ -438,7 +419,6 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             // barrier and wait for them below.
             if (wave == 4) wait_item(NA + min(h, nch - 1));
             else asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            LY_TSS(32 * (wave - 2) + 2 * h);
             if (h == 0) gelu_tab_build(gelu_s, lt, 256);   // every computing wave holds its fragments of LayerNorm2(x') by now; first used in step 1
             // At_k of the qkv linear: at_s is idle since the shrink of phase A, and a request made here does not queue up
             // behind the first chunks of C
@@ -478,13 +458,9 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            LY_TSS(32 * (wave - 2) + 2 * h + 1);
         }
-        LY_TS(8);
         wait_item(NA + nch - 1);                                                // Be: every chunk and slice of B is consumed
-        LY_TSS(203 + 10 * (wave - 4));
         refill(HAS_QKV ? PC - 1 : 0, HAS_QKV ? PC + 1 : -1);                    // (the tile still needs stages 0-2)
-        LY_TSS(204 + 10 * (wave - 4));
         if (second) {
 #pragma unroll
             for (int rt = 0; rt < 2; ++rt) {
@@ -496,9 +472,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
                         *(f32x4 *)(trow + (ct * 32 + 8 * g4) * 4) = f32x4{y[rt][ct][4 * g4], y[rt][ct][4 * g4 + 1], y[rt][ct][4 * g4 + 2], y[rt][ct][4 * g4 + 3]};
             }
         }
-        LY_TSS(200 + 10 * (wave - 4));
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // By: the y tile is complete
-        LY_TSS(201 + 10 * (wave - 4));
         add_tile();                                                             // x'' = x' + y
         if (HAS_QKV) {
             // Bt: the tile is dead.  Chunks 2-4 of C (stages 0-2) are requested now, by a computing wave: requested by a
@@ -515,9 +489,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
                 for (int i = 0; i < KT; ++i) *(f32x4 *)(dst + 64 * i) = xr[k * KT + i];
             }
         }
-        LY_TSS(202 + 10 * (wave - 4));
         if (HAS_QKV) ln_rows(gbq_s);
-        LY_TS(9);
     } else {
         load_fa();
         f32x16 hb[2];                            // first product of chunks h / h - 1: row lm, columns wc*32 + 8*(e/4) + 4*lh + e%4
@@ -526,7 +498,6 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             constexpr int par = decltype(PAR)::value ? 1 : 0;          // h & 1
             f32x16 &hout = hb[par], &hin = hb[par ^ 1];
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            LY_TSS(32 + 2 * h);
             const bf16_t *s1 = Ws + ((SB0 + h) & 3) * IT_EL;                                        // W1(h)
             bf16_t *Hw = Hs + ((h - 1) & 1) * 4096;                                                  // chunk h - 1
             bf16x8 f1[2][KT];
@@ -568,7 +539,6 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            LY_TSS(32 + 2 * h + 1);
         };
         first_step(T_{}, F_{}, F_{}, 0);
         for (int h = 1; h < nch; ++h) {
@@ -578,9 +548,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
         if (nch & 1) first_step(F_{}, T_{}, T_{}, nch);
         else first_step(F_{}, T_{}, F_{}, nch);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // step nch + 1: the other waves' last product
-        LY_TS(8);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // Be: the ring positions of B are consumed
-        LY_TS(9);
         asm volatile("s_barrier" ::: "memory");                                 // By
         if (HAS_QKV) {
             asm volatile("s_barrier" ::: "memory");                             // Bt
@@ -592,7 +560,6 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
 
     // ================================================================ phase C: qkv = LayerNorm1'(x'') Wq + bq + lora
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");             // Bz: LayerNorm1'(x'') is in As, the tile is dead
-    LY_TS(10);
     f32x16 acc[LY_MAXCH + 1];                    // acc[c][e]: row wr*32 + lm, column c*64 + wc*32 + 8*(e/4) + 4*lh + e%4
     const int i0q = NA + nch;                    // first item of C
     if (loader) {
@@ -620,7 +587,6 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             if (2 * s + 1 < nchq) linear_step(acc[2 * s], acc[2 * s + 1], 2 * s, PC + 2 * s, Nq, bq_s, std::true_type{});
             else if (2 * s < nchq) linear_step(acc[2 * s], acc[2 * s], 2 * s, PC + 2 * s, Nq, bq_s, std::false_type{});
         }
-        LY_TS(11);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");         // Bf2
         if (lora_q) {
             // all operands first, then the MFMAs (one read-then-multiply per chunk would pay the LDS latency nine times)
@@ -652,9 +618,7 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             }
         }
     }
-    LY_TS(12);
     __syncthreads();
-    LY_TS(13);
     {
         const int qstride = ((Nq * 2 + 255) & ~255) + 16, pieces = (Nq * 2) >> 4;
         char *out = (char *)a.qkv_out + ((size_t)ob * a.T + t0) * Nq * 2;
@@ -663,14 +627,12 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
             *(f32x4 *)(out + (size_t)row * Nq * 2 + p * 16) = *(const f32x4 *)((const char *)lds + row * qstride + p * 16);
         }
     }
-    LY_TS(14);
-    LY_TS_END;
 }
 
 template <int KT, bool HAS_PROJ, bool HAS_QKV> int launch_layer_t(const RowLayerArgs &a, hipStream_t st)
 {
     constexpr int D = 64 * KT;
-    constexpr int LDS = ((KT < 2 ? 2 : KT) + LY_NS * KT) * 64 * 64 * 2 + (LY_MAX_DM + LY_MAX_NQ + 2 * D + 4 * D) * 4 + 16 * LY_AT_STRIDE * 2 + (KT == 3 ? 0 : GELU_TAB_ENTRIES * 8) + LY_TS_BYTES;
+    constexpr int LDS = ((KT < 2 ? 2 : KT) + LY_NS * KT) * 64 * 64 * 2 + (LY_MAX_DM + LY_MAX_NQ + 2 * D + 4 * D) * 4 + 16 * LY_AT_STRIDE * 2 + (KT == 3 ? 0 : GELU_TAB_ENTRIES * 8);
     static_assert(LDS <= 160 * 1024, "LDS budget");
     auto kern = rowlayer_kernel<KT, HAS_PROJ, HAS_QKV>;
     if (LDS > 64 * 1024) {

@@ -24,13 +24,6 @@
 
 #include <type_traits>
 
-// phase timestamps for tuning; a test harness defines the macros before including this file
-#ifndef RL_TS
-#define RL_TS(i)
-#define RL_TS_END
-#define RL_TS_BYTES 0
-#endif
-
 namespace {
 
 constexpr int RL_ROWS = 64;    // token rows per workgroup
@@ -54,7 +47,6 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
     float *dump_s = bias_s + RL_MAXCH * RL_BNC;             // 64 words nobody reads (target of the L2 warm-up loads)
     float *gb_s = dump_s + 64;                              // LayerNorm gain [K] and shift [K]
 
-    RL_TS(0);
     const int tiles = (a.T + RL_ROWS - 1) / RL_ROWS;
     const int ob = blockIdx.x / tiles, t0 = (blockIdx.x % tiles) * RL_ROWS;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -106,7 +98,6 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
         for (int j = 0; j < (RL_MAXCH * RL_BNC + 255) / 256; ++j) bv[j] = a.bias ? a.bias[min(tid + 256 * j, a.N - 1)] : 0.f;   // no per-lane condition: see ln_gb_load
     }
 
-    RL_TS(1);
     const int n_out = a.n_out_dev ? min(*a.n_out_dev, a.n_out) : a.n_out;
     if (ob >= n_out) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -114,7 +105,6 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
     }
     const int xb = a.in_block_of_out ? a.in_block_of_out[ob] : ob;
     const int k_ad = (a.At && a.adapter_of_out) ? a.adapter_of_out[ob] : -1;
-    RL_TS(2);
     // the W stream (workgroups past the block count have left without moving data): only the chunks of step 0 for now --
     // the activation rows are still on their way and would be slowed down by more; the rest of the ring follows at
     // the first barrier, which the computing waves reach once their loads have arrived
@@ -146,9 +136,7 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
             for (int q = last + 1; q < min(RL_NS, nchunks); ++q) issue_w(q);
             last = min(RL_NS, nchunks) - 1;
         }
-        RL_TS(3);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // activation rows are in LDS
-        RL_TS(4);
         for (int sp = 0; 2 * sp < nchunks; ++sp) {
             // step sp multiplies chunks 2 sp and 2 sp + 1: they must have landed; newer ones may stay in flight (loads
             // complete in issue order)
@@ -165,14 +153,11 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
                     if (i0 + lane < n16) glds16(bsrc + (size_t)(i0 + lane) * 16, __builtin_amdgcn_readfirstlane(lds_addr_of(As) + i0 * 16));
             }
             // every wave is past the chunks of step sp - 1: refill the ring behind them
-            RL_TS(10 + sp);
             const int upto = min(2 * sp - 1 + RL_NS, nchunks - 1);
             for (int q = last + 1; q <= upto; ++q) issue_w(q);
             last = max(last, upto);
         }
-        RL_TS(5);
         rl_wait_barrier<0>();                                             // Bt_k has landed; the ring is dead
-        RL_TS(6);
         asm volatile("s_barrier" ::: "memory");                           // expand done: Bt_k is dead
     } else {
         // ================================================================ computing waves
@@ -199,9 +184,7 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // gain and shift are in LDS
             ln_finish<KT, 4>(xv, gb_s, a.eps, As, tid);
         }
-        RL_TS(3);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        RL_TS(4);
 
         // activation fragments -> registers (B operand of the transposed product): rows wr*32 + lm
         bf16x8 fa[KT * 4];
@@ -236,7 +219,6 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
         auto stream_step = [&](int c0, auto PAIR) {
             constexpr bool pair = decltype(PAIR)::value;
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            RL_TS(10 + (c0 >> 1));
             const bf16_t *st0 = Ws + (c0 % RL_NS) * W_EL, *st1 = Ws + ((c0 + 1) % RL_NS) * W_EL;
             bf16x8 fw0[2][KT], fw1[2][KT];
             auto load = [&](int kk, int sl) {
@@ -270,9 +252,7 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
                 stream_step(2 * sp, std::false_type{});
             }
         }
-        RL_TS(5);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // Bt_k has landed; every wave is done with the ring
-        RL_TS(6);
         // expand: lane (column, lh) supplies ranks 4*lh + {0..3} and 8 + 4*lh + {0..3} of Bt_k's row, the order the shrink left in fs
         if (k_ad >= 0) {
             // r is a multiple of 4: each half of the operand is one 8-byte read, at a clamped offset and zeroed where the
@@ -317,9 +297,7 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
             else if (c < nchunks) stage_chunk(c, std::false_type{});
         }
     }
-    RL_TS(7);
     __syncthreads();
-    RL_TS(8);
     char *out = (char *)a.out + ((size_t)ob * a.T + t0) * row_bytes;
     if (f32out) {
         // the loader threads hold the residual pieces; they finish the tile alone
@@ -341,13 +319,11 @@ __global__ __launch_bounds__(RL_THREADS) void rowlin_kernel(const RowLinArgs a)
             *(f32x4 *)(out + (size_t)row * row_bytes + p * 16) = *(const f32x4 *)(tile + row * stride + p * 16);
         }
     }
-    RL_TS(9);
-    RL_TS_END;
 }
 
 template <int KT, int MODE> int launch_kt_mode(const RowLinArgs &a, hipStream_t st)
 {
-    constexpr int LDS = (KT * RL_ROWS * 64 + RL_NS * KT * RL_BNC * 64) * 2 + RL_MAXCH * RL_BNC * 4 + 256 + KT * 512 + RL_TS_BYTES;   // + dump words of the L2 warm-up, LayerNorm gain and shift
+    constexpr int LDS = (KT * RL_ROWS * 64 + RL_NS * KT * RL_BNC * 64) * 2 + RL_MAXCH * RL_BNC * 4 + 256 + KT * 512;   // + dump words of the L2 warm-up, LayerNorm gain and shift
     auto kern = rowlin_kernel<KT, MODE>;
     if (LDS > 64 * 1024) {
         static bool attr_set = false;   // raising the dynamic LDS limit is a per-kernel, process-wide setting

@@ -268,6 +268,37 @@ def stream_step(cfg, w, frames, base_w, base_b, membership, carry, state: Option
     return out
 
 
+# ------------------------------------- context construction (Alg. 1) and its metrics
+
+def build_contexts(cooc, B: int, M_max: int, allow_overlap: bool = False):
+    """Alg. 1 on a [K, K] co-occurrence matrix.  Returns (membership uint8 [M, K], n_unplaced)."""
+    cooc, cp = _f32(cooc)
+    K = cooc.shape[0]
+    assert cooc.shape == (K, K)
+    mem = np.zeros((max(M_max, 1), K), dtype=np.uint8)
+    unplaced = C.c_int32(0)
+    M = lib().ora_build_contexts(cp, K, B, M_max, int(allow_overlap), mem.ctypes.data_as(C.POINTER(C.c_uint8)), C.byref(unplaced))
+    return mem[:M].copy(), int(unplaced.value)
+
+
+def intra_coherence(cooc, membership, norm: float = 1.0) -> float:
+    """Eq. 6 with co(i, j) = cooc[i, j] / norm."""
+    cooc, cp = _f32(cooc)
+    mem = np.ascontiguousarray(membership, dtype=np.uint8)
+    f = lib().ora_intra_coherence
+    f.restype = C.c_double
+    return float(f(cp, cooc.shape[0], C.c_double(norm), mem.ctypes.data_as(C.POINTER(C.c_uint8)), mem.shape[0]))
+
+
+def stream_metrics(row_offsets, adapter_ids, M: int):
+    """(AvgCoverage, SwitchPenalty) of a stream of context sets given as CSR arrays (Sec. 3.4)."""
+    off, offp = _i32(row_offsets)
+    ids, idsp = _i32(adapter_ids if len(adapter_ids) else np.zeros(1, dtype=np.int32))
+    cov = C.c_double(0.0); sw = C.c_int64(0)
+    lib().ora_stream_metrics(offp, idsp, len(off) - 1, M, C.byref(cov), C.byref(sw))
+    return float(cov.value), int(sw.value)
+
+
 # ------------------------------------------------- shape accounting (Table 2)
 
 def count_params(cfg, n_classes_base_head: int = 0) -> int:

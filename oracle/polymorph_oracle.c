@@ -417,3 +417,121 @@ int ora_select(const float *scores, int F, int K, const uint8_t *member, int M, 
     free(order); free(size); free(Y); free(Yprev); free(U); free(S); free(Sprev);
     return total > cap ? -1 : 0;
 }
+
+/* ------------------------------------------- context construction (Alg. 1) */
+
+/* Alg. 1 "BuildContexts" (Sec. 3.4) on a co-occurrence matrix cooc[K][K] (cooc[i][j], i != j: how often labels i
+ * and j occur together; cooc[l][l]: how often l occurs at all).  Steps, in the order of the listing:
+ *   - a label is valid iff its row has a non-zero entry;
+ *   - valid labels are visited by descending frequency cooc[l][l] (ties: lower index first) -- the text builds the
+ *     clusters "around frequently occurring labels";
+ *   - without overlap a label that is already assigned is skipped;
+ *   - the cluster around l is l plus its strongest co-occurring neighbours: up to B - 1 labels j != l with
+ *     cooc[l][j] > 0, strongest first (ties: lower index), without overlap only labels not yet assigned;
+ *   - the cluster is added iff the same label set is not a context already and fewer than M_max contexts exist;
+ *     without overlap its labels become assigned;
+ *   - afterwards every valid label that is in no context (same visiting order) is put into the context with
+ *     fewer than B labels to which it fits best: largest sum of cooc[l][j] over the context's labels j (ties:
+ *     lower context index).  If no context has room the label stays out and is counted in n_unplaced.
+ * member[M_max][K] receives the contexts as 0/1 rows in order of creation; returns their number. */
+int ora_build_contexts(const float *cooc, int K, int B, int M_max, int allow_overlap, uint8_t *member,
+                       int32_t *n_unplaced)
+{
+    int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
+    uint8_t *valid = (uint8_t *)malloc((size_t)K), *assigned = (uint8_t *)calloc((size_t)K, 1);
+    uint8_t *cluster = (uint8_t *)malloc((size_t)K);
+    int nv = 0, M = 0;
+    for (int l = 0; l < K; ++l) {
+        valid[l] = 0;
+        for (int j = 0; j < K; ++j) if (cooc[(size_t)l * K + j] != 0.f) valid[l] = 1;
+        if (valid[l]) order[nv++] = l;
+    }
+    for (int i = 1; i < nv; ++i) { /* stable insertion sort by descending frequency */
+        int l = order[i], j = i - 1;
+        while (j >= 0 && cooc[(size_t)order[j] * K + order[j]] < cooc[(size_t)l * K + l]) { order[j + 1] = order[j]; --j; }
+        order[j + 1] = l;
+    }
+    memset(member, 0, (size_t)M_max * K);
+    for (int i = 0; i < nv; ++i) {
+        const int l = order[i];
+        if (!allow_overlap && assigned[l]) continue;
+        memset(cluster, 0, (size_t)K);
+        cluster[l] = 1;
+        for (int n = 1; n < B; ++n) { /* next strongest neighbour that is still free */
+            int best = -1;
+            for (int j = 0; j < K; ++j) {
+                if (cluster[j] || cooc[(size_t)l * K + j] <= 0.f) continue;
+                if (!allow_overlap && assigned[j]) continue;
+                if (best < 0 || cooc[(size_t)l * K + j] > cooc[(size_t)l * K + best]) best = j;
+            }
+            if (best < 0) break;
+            cluster[best] = 1;
+        }
+        int unique = 1;
+        for (int c = 0; c < M; ++c) if (memcmp(member + (size_t)c * K, cluster, (size_t)K) == 0) unique = 0;
+        if (unique && M < M_max) {
+            memcpy(member + (size_t)M * K, cluster, (size_t)K);
+            ++M;
+            if (!allow_overlap) for (int j = 0; j < K; ++j) if (cluster[j]) assigned[j] = 1;
+        }
+    }
+    int unplaced = 0;
+    for (int i = 0; i < nv; ++i) {
+        const int l = order[i];
+        int covered = 0;
+        for (int c = 0; c < M; ++c) covered |= member[(size_t)c * K + l];
+        if (covered) continue;
+        int best = -1;
+        double best_fit = 0.0;
+        for (int c = 0; c < M; ++c) {
+            int size = 0;
+            double fit = 0.0;
+            for (int j = 0; j < K; ++j)
+                if (member[(size_t)c * K + j]) { ++size; fit += (double)cooc[(size_t)l * K + j]; }
+            if (size >= B) continue;
+            if (best < 0 || fit > best_fit) { best = c; best_fit = fit; }
+        }
+        if (best >= 0) member[(size_t)best * K + l] = 1; else ++unplaced;
+    }
+    if (n_unplaced) *n_unplaced = unplaced;
+    free(order); free(valid); free(assigned); free(cluster);
+    return M;
+}
+
+/* IntraCoherence (Eq. 6): mean over the contexts of the mean of co(i, j) over ordered pairs i != j of the context,
+ * co(i, j) = cooc[i][j] / norm.  A context with fewer than two labels has no pair and contributes 0. */
+double ora_intra_coherence(const float *cooc, int K, double norm, const uint8_t *member, int M)
+{
+    if (M <= 0) return 0.0;
+    double total = 0.0;
+    for (int c = 0; c < M; ++c) {
+        int size = 0;
+        double sum = 0.0;
+        for (int i = 0; i < K; ++i) {
+            if (!member[(size_t)c * K + i]) continue;
+            ++size;
+            for (int j = 0; j < K; ++j)
+                if (j != i && member[(size_t)c * K + j]) sum += (double)cooc[(size_t)i * K + j] / norm;
+        }
+        if (size >= 2) total += sum / ((double)size * (size - 1));
+    }
+    return total / M;
+}
+
+/* AvgCoverage = (1/T) sum_t |S_t| and SwitchPenalty = sum_{t >= 2} [S_t != S_{t-1}] (Sec. 3.4) of a stream of
+ * context sets given as CSR arrays; sets are compared as sets (the order inside a frame does not matter). */
+void ora_stream_metrics(const int32_t *row_offsets, const int32_t *adapter_ids, int F, int M, double *avg_coverage,
+                        int64_t *switch_penalty)
+{
+    uint8_t *cur = (uint8_t *)calloc((size_t)M, 1), *prev = (uint8_t *)calloc((size_t)M, 1);
+    int64_t switches = 0;
+    for (int t = 0; t < F; ++t) {
+        memset(cur, 0, (size_t)M);
+        for (int i = row_offsets[t]; i < row_offsets[t + 1]; ++i) cur[adapter_ids[i]] = 1;
+        if (t > 0 && memcmp(cur, prev, (size_t)M) != 0) ++switches;
+        memcpy(prev, cur, (size_t)M);
+    }
+    *avg_coverage = F > 0 ? (double)row_offsets[F] / F : 0.0;
+    *switch_penalty = switches;
+    free(cur); free(prev);
+}

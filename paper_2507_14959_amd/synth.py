@@ -331,3 +331,62 @@ def make_cover_instance(seed: int, K: int, M: int, max_size: int, partition: boo
             mem[m, rng.choice(K, size=n, replace=False)] = 1
     acc = rng.random((M, K), dtype=np.float32) if with_acc else None
     return mem, acc
+
+
+# ----------------------------------------------------------------------------
+# co-occurrence matrix and accuracy table (context construction, overlapping contexts)
+# ----------------------------------------------------------------------------
+
+def make_cooccurrence(n_groups: int = 16, group_size: int = 5, n_images: int = 20000, p_partner: float = 0.0,
+                      p_extra: float = 0.15, seed: int = 2001, shuffle: bool = True):
+    """Counts of a synthetic training set with planted label groups, in place of the COCO co-occurrence matrix.
+
+    Every image shows 1-3 labels of one planted group (groups have a Zipf-like popularity); each shown label brings its
+    fixed partner label from another group along with probability p_partner (cross-group structure: with it the
+    neighbourhoods of the labels of one group differ, which is what makes overlapping contexts distinct); with
+    probability p_extra one label from anywhere is added.  cooc[i, j] (i != j) = images showing both, cooc[l, l] =
+    images showing l.  Returns (cooc float32 [K, K], planted list of label lists, n_images).  With `shuffle` the
+    label ids are permuted so that the planted groups are not runs of consecutive ids.
+    """
+    rng = np.random.default_rng(seed)
+    K = n_groups * group_size
+    perm = rng.permutation(K) if shuffle else np.arange(K)
+    planted = [[int(perm[g * group_size + i]) for i in range(group_size)] for g in range(n_groups)]
+    group_of = np.zeros(K, dtype=np.int64)
+    for g, ls in enumerate(planted):
+        group_of[ls] = g
+    partner = np.zeros(K, dtype=np.int64)
+    for l in range(K):
+        while True:
+            c = int(rng.integers(0, K))
+            if group_of[c] != group_of[l]:
+                partner[l] = c
+                break
+    pop = (np.arange(n_groups) + 1.0) ** -0.7
+    pop /= pop.sum()
+    cooc = np.zeros((K, K), dtype=np.float64)
+    groups = rng.choice(n_groups, size=n_images, p=pop)
+    counts = rng.integers(1, 4, size=n_images)
+    extra = rng.random(n_images) < p_extra
+    extra_label = rng.integers(0, K, size=n_images)
+    for g, n, e, el in zip(groups, counts, extra, extra_label):
+        shown = [int(x) for x in rng.choice(planted[g], size=int(n), replace=False)]
+        labels = set(shown)
+        for l in shown:
+            if p_partner > 0.0 and rng.random() < p_partner:
+                labels.add(int(partner[l]))
+        if e:
+            labels.add(int(el))
+        labels = sorted(labels)
+        for a in labels:
+            for b in labels:
+                cooc[a, b] += 1.0
+    return cooc.astype(np.float32), planted, n_images
+
+
+def make_accuracy_table(membership: np.ndarray, seed: int = 2002, lo: float = 0.05, hi: float = 1.0) -> np.ndarray:
+    """A synthetic a_{C,l} table [M, K]: uniform in [lo, hi) where label l is in context C, 0 elsewhere (in place of the
+    per-class validation accuracies of trained adapters)."""
+    rng = np.random.default_rng(seed)
+    acc = (lo + (hi - lo) * rng.random(membership.shape, dtype=np.float32)).astype(np.float32)
+    return np.where(membership != 0, acc, np.float32(0.0)).astype(np.float32)

@@ -234,6 +234,35 @@ int poly_lora_linear(const void *X, int n_xblocks, int T, int Kdim, const void *
                      int32_t *dev_status, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Offline half of the selector, on HOST memory (no device work, no stream): context construction and the quality
+ * metrics of Sec. 3.4.
+ *
+ * poly_build_contexts -- Alg. 1: label contexts from a co-occurrence matrix.
+ *   cooc [K][K] float, host: cooc[i][j] (i != j) = how often labels i and j occur together, cooc[l][l] = how often
+ *   l occurs.  A label is valid iff its row has a non-zero entry.  Valid labels are visited by descending
+ *   cooc[l][l] (ties: lower id); a visited label (skipped when overlap is off and it is assigned already) forms a
+ *   cluster with its up to B - 1 strongest neighbours (cooc[l][j] > 0, ties: lower id; overlap off: unassigned
+ *   labels only); the cluster becomes a context iff no equal context exists and fewer than M_max exist.  Valid
+ *   labels left in no context are then put, in the same order, into the context with fewer than B labels that
+ *   maximises the sum of cooc[l][j] over its labels (ties: lower context id); labels for which no context has room
+ *   are counted in n_unplaced (nullable).
+ *   group_membership [M_max][K] uint8, host, out (rows past *n_contexts are zero): the layout poly_select reads.
+ *   K <= 1024, M_max <= 64, B >= 1.  Errors: POLY_EINVAL.
+ *
+ * poly_intra_coherence -- Eq. 6: mean over contexts of the mean of co(i, j) = cooc[i][j] / norm over ordered pairs
+ *   i != j inside the context; contexts with fewer than two labels contribute 0.
+ *
+ * poly_stream_metrics -- AvgCoverage = (1/F) sum_t |S_t| and SwitchPenalty = sum_{t >= 1} [S_t != S_{t-1}] (Sec. 3.4)
+ *   of the context sets that poly_select wrote (CSR arrays copied to the host); sets compare as sets.
+ *   Errors: POLY_EINVAL, POLY_ERANGE (ids outside [0, M), offsets not monotone).
+ */
+int poly_build_contexts(const float *cooc, int K, int B, int M_max, int allow_overlap, uint8_t *group_membership,
+                        int32_t *n_contexts, int32_t *n_unplaced);
+int poly_intra_coherence(const float *cooc, int K, double norm, const uint8_t *group_membership, int M, double *out);
+int poly_stream_metrics(const int32_t *row_offsets, const int32_t *adapter_ids, int F, int M, double *avg_coverage,
+                        int64_t *switch_penalty);
+
+/* ------------------------------------------------------------------------------------------
  * poly_lora_linear_static -- poly_lora_linear for callers that cannot allocate device memory (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels and same results, but
  * the scratch memory (bookkeeping words, row maps, shrink output S) is a device array of POLY_STATIC_SCRATCH_BYTES

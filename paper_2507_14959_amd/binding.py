@@ -22,7 +22,8 @@ LIB_PATH = os.path.join(_HERE, "libpoly.so")
 
 EXPORTS = ("poly_status_string", "poly_select_state_bytes", "poly_select", "poly_forward_workspace_bytes",
            "poly_forward", "poly_stream_step_workspace_bytes", "poly_stream_step", "poly_lora_linear_workspace_bytes",
-           "poly_lora_linear", "poly_lora_linear_static", "poly_profile_begin", "poly_profile_end")
+           "poly_lora_linear", "poly_lora_linear_static", "poly_build_contexts", "poly_intra_coherence", "poly_stream_metrics",
+           "poly_profile_begin", "poly_profile_end")
 STATIC_SCRATCH_BYTES = 4 * 1024 * 1024
 STAGES = ("select", "gemm", "shrink", "attention", "layernorm", "other")
 
@@ -99,6 +100,13 @@ def lib():
                                        C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.poly_lora_linear_static.restype = C.c_int
         L.poly_lora_linear_static.argtypes = L.poly_lora_linear.argtypes[:18] + [C.c_void_p]
+        L.poly_build_contexts.restype = C.c_int
+        L.poly_build_contexts.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_int32),
+                                          C.POINTER(C.c_int32)]
+        L.poly_intra_coherence.restype = C.c_int
+        L.poly_intra_coherence.argtypes = [C.c_void_p, C.c_int, C.c_double, C.c_void_p, C.c_int, C.POINTER(C.c_double)]
+        L.poly_stream_metrics.restype = C.c_int
+        L.poly_stream_metrics.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.poly_profile_begin.restype = C.c_int
         L.poly_profile_begin.argtypes = [C.c_int]
         L.poly_profile_end.restype = C.c_int
@@ -293,6 +301,43 @@ def poly_lora_linear_static(X: torch.Tensor, Wt: torch.Tensor, bias: Optional[to
     if check and rc != POLY_OK:
         raise PolyError(rc, "poly_lora_linear_static")
     return rc
+
+
+# ---- offline half of the selector (host arrays)
+
+def poly_build_contexts(cooc: np.ndarray, B: int, M_max: int, allow_overlap: bool = False, check: bool = True):
+    """Alg. 1 on a host co-occurrence matrix [K, K].  Returns (membership uint8 [M, K], n_unplaced)."""
+    cooc = np.ascontiguousarray(cooc, dtype=np.float32)
+    K = cooc.shape[0]
+    mem = np.zeros((max(M_max, 1), K), dtype=np.uint8)
+    n_ctx, n_unplaced = C.c_int32(0), C.c_int32(0)
+    rc = lib().poly_build_contexts(cooc.ctypes.data, K, B, M_max, int(allow_overlap), mem.ctypes.data, C.byref(n_ctx), C.byref(n_unplaced))
+    if rc != POLY_OK:
+        if check:
+            raise PolyError(rc, "poly_build_contexts")
+        return rc
+    return mem[:n_ctx.value].copy(), int(n_unplaced.value)
+
+
+def poly_intra_coherence(cooc: np.ndarray, membership: np.ndarray, norm: float = 1.0) -> float:
+    cooc = np.ascontiguousarray(cooc, dtype=np.float32)
+    mem = np.ascontiguousarray(membership, dtype=np.uint8)
+    out = C.c_double(0.0)
+    rc = lib().poly_intra_coherence(cooc.ctypes.data, cooc.shape[0], float(norm), mem.ctypes.data, mem.shape[0], C.byref(out))
+    if rc != POLY_OK:
+        raise PolyError(rc, "poly_intra_coherence")
+    return float(out.value)
+
+
+def poly_stream_metrics(row_offsets: np.ndarray, adapter_ids: np.ndarray, M: int):
+    """(AvgCoverage, SwitchPenalty) of host CSR arrays."""
+    off = np.ascontiguousarray(row_offsets, dtype=np.int32)
+    ids = np.ascontiguousarray(adapter_ids, dtype=np.int32)
+    cov, sw = C.c_double(0.0), C.c_int64(0)
+    rc = lib().poly_stream_metrics(off.ctypes.data, ids.ctypes.data if ids.size else None, len(off) - 1, M, C.byref(cov), C.byref(sw))
+    if rc != POLY_OK:
+        raise PolyError(rc, "poly_stream_metrics")
+    return float(cov.value), int(sw.value)
 
 
 def poly_profile_begin(max_launches: int) -> None:

@@ -148,8 +148,14 @@ def _pack(cfg, w: Dict[str, np.ndarray], L0: int):
 
 
 def forward(cfg, w, frames, row_offsets, adapter_ids, L0: Optional[int] = None, merged: bool = False,
-            K: int = 0, want_x: bool = False):
-    """Scores of every (frame, adapter) row-block.  Returns dict(logits, scores, merged, x)."""
+            K: int = 0, want_x: bool = False, compose: str = "branch"):
+    """Scores of every (frame, adapter) row-block.  Returns dict(logits, scores, merged, x).
+
+    compose = "branch": every (frame, adapter) pair is its own branch with that adapter alone (x is [R, T, D]);
+    compose = "sum": one hidden state per frame with all of its adapters summed on top of the shared weights, then
+    every active adapter's head on that state (x is [F, T, D]).
+    """
+    assert compose in ("branch", "sum")
     L0 = cfg.L0 if L0 is None else L0
     m, ws, keep = _pack(cfg, w, L0)
     frames, fp = _f32(frames)
@@ -158,9 +164,10 @@ def forward(cfg, w, frames, row_offsets, adapter_ids, L0: Optional[int] = None, 
     R = int(off[F])
     logits = np.zeros((R, cfg.C)); scores = np.zeros((R, cfg.C))
     mo = np.zeros((F, K)) if K else None
-    xf = np.zeros((R, cfg.T, cfg.D)) if want_x else None
+    xf = np.zeros((R if compose == "branch" else F, cfg.T, cfg.D)) if want_x else None
     dp = C.POINTER(C.c_double)
-    rc = lib().ora_forward(C.byref(m), C.byref(ws), fp, F, offp, idsp, int(merged),
+    fn = lib().ora_forward if compose == "branch" else lib().ora_forward_sum
+    rc = fn(C.byref(m), C.byref(ws), fp, F, offp, idsp, int(merged),
                            logits.ctypes.data_as(dp), scores.ctypes.data_as(dp),
                            mo.ctypes.data_as(dp) if K else None, K,
                            xf.ctypes.data_as(dp) if want_x else None)

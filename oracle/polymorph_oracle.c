@@ -20,6 +20,12 @@
  *                         forward rebuilt from library routines;
  *   ora_forward        -> zero-B = bare backbone, unmerged = merged (Sec. 3.1),
  *                         position invariance, L0 consistency, Table 2 counts;
+ *   ora_forward_sum    -> one adapter per frame = ora_forward (bitwise), equals the forward
+ *                         with W + sum_k s A_k B_k merged, a forward rebuilt from library
+ *                         routines with the summed weights, order of a frame's ids irrelevant;
+ *   ora_build_contexts, ora_intra_coherence, ora_stream_metrics
+ *                      -> hand-worked examples, planted groups, a second writing of Alg. 1,
+ *                         brute force on small label sets, closed forms (Eq. 6);
  *   ora_select         -> brute force over all context subsets (Eq. 2), the
  *                         closed form on partitions, a second naive writing
  *                         of Alg. 2.
@@ -160,30 +166,37 @@ void ora_patch_embed(const float *frame, int H, int W, int p, int D, const float
 static int tgt_din(const ora_model *m, int t) { return t == 3 ? m->Dm : m->D; }
 static int tgt_dout(const ora_model *m, int t) { return t == 0 ? 3 * m->D : (t == 2 ? m->Dm : m->D); }
 
-/* One linear of layer `layer` (target t: 0 qkv, 1 proj, 2 fc1, 3 fc2) for adapter k (k < 0: none).
- * merged = 0: y = x W + b + s (x A_k) B_k.   merged = 1: y = x (W + s A_k B_k) + b. */
-static void adapted_linear(const ora_model *m, const ora_weights *w, int t, int layer, int k, int merged,
+/* One linear of layer `layer` (target t: 0 qkv, 1 proj, 2 fc1, 3 fc2) with the adapters ks[0 .. nk) on top (nk = 0: none).
+ * merged = 0: y = x W + b + sum_k s (x A_k) B_k   -- "summed on top without merging", Sec. 3.1; one adapter in the branch reading.
+ * merged = 1: y = x (W + sum_k s A_k B_k) + b. */
+static void adapted_linear(const ora_model *m, const ora_weights *w, int t, int layer, const int32_t *ks, int nk, int merged,
                            const double *x, int rows, const float *W, const float *b, double *y)
 {
     const int din = tgt_din(m, t), dout = tgt_dout(m, t), r = m->r;
-    const int on = k >= 0 && layer >= m->L0 && (m->targets & (1 << t)) && w->A[t] && w->B[t];
+    const int on = nk > 0 && layer >= m->L0 && (m->targets & (1 << t)) && w->A[t] && w->B[t];
     if (!on) { ora_linear(x, rows, din, W, b, dout, y); return; }
-    const size_t slot = (size_t)(layer - m->L0) * m->n_adapters + k;
-    const float *A = w->A[t] + slot * din * r;
-    const float *B = w->B[t] + slot * r * dout;
     if (!merged) {
         ora_linear(x, rows, din, W, b, dout, y);
-        ora_lora_add(x, rows, din, A, r, B, dout, m->lora_scale, y);
+        for (int a = 0; a < nk; ++a) {
+            const size_t slot = (size_t)(layer - m->L0) * m->n_adapters + ks[a];
+            ora_lora_add(x, rows, din, w->A[t] + slot * din * r, r, w->B[t] + slot * r * dout, dout, m->lora_scale, y);
+        }
         return;
     }
-    /* W' = W + s A B written out, then the plain linear in double */
+    /* W' = W + s sum_k A_k B_k written out, then the plain linear in double */
     double *Wm = (double *)malloc(sizeof(double) * (size_t)din * dout);
-    for (int i = 0; i < din; ++i)
-        for (int n = 0; n < dout; ++n) {
-            double acc = 0.0;
-            for (int j = 0; j < r; ++j) acc += (double)A[(size_t)i * r + j] * (double)B[(size_t)j * dout + n];
-            Wm[(size_t)i * dout + n] = (double)W[(size_t)i * dout + n] + m->lora_scale * acc;
-        }
+    for (size_t i = 0; i < (size_t)din * dout; ++i) Wm[i] = (double)W[i];
+    for (int a = 0; a < nk; ++a) {
+        const size_t slot = (size_t)(layer - m->L0) * m->n_adapters + ks[a];
+        const float *A = w->A[t] + slot * din * r;
+        const float *B = w->B[t] + slot * r * dout;
+        for (int i = 0; i < din; ++i)
+            for (int n = 0; n < dout; ++n) {
+                double acc = 0.0;
+                for (int j = 0; j < r; ++j) acc += (double)A[(size_t)i * r + j] * (double)B[(size_t)j * dout + n];
+                Wm[(size_t)i * dout + n] += m->lora_scale * acc;
+            }
+    }
     for (int i = 0; i < rows; ++i) {
         double *yi = y + (size_t)i * dout;
         for (int n = 0; n < dout; ++n) yi[n] = (double)b[n];
@@ -193,8 +206,8 @@ static void adapted_linear(const ora_model *m, const ora_weights *w, int t, int 
     free(Wm);
 }
 
-/* One pre-LN transformer block in place on x[T][D]; adapter k (or -1). */
-static void block_layer(const ora_model *m, const ora_weights *w, int layer, int k, int merged, int T, double *x)
+/* One pre-LN transformer block in place on x[T][D] with the adapters ks[0 .. nk) on its linears. */
+static void block_layer(const ora_model *m, const ora_weights *w, int layer, const int32_t *ks, int nk, int merged, int T, double *x)
 {
     const int D = m->D, Dm = m->Dm;
     double *u = (double *)malloc(sizeof(double) * (size_t)T * D);
@@ -204,18 +217,18 @@ static void block_layer(const ora_model *m, const ora_weights *w, int layer, int
     double *h = (double *)malloc(sizeof(double) * (size_t)T * Dm);
 
     ora_layernorm(x, T, D, w->ln1_g + (size_t)layer * D, w->ln1_b + (size_t)layer * D, m->ln_eps, u);
-    adapted_linear(m, w, 0, layer, k, merged, u, T, w->qkv_w + (size_t)layer * D * 3 * D,
+    adapted_linear(m, w, 0, layer, ks, nk, merged, u, T, w->qkv_w + (size_t)layer * D * 3 * D,
                    w->qkv_b + (size_t)layer * 3 * D, qkv);
     ora_attention(qkv, T, D, m->heads, o);
-    adapted_linear(m, w, 1, layer, k, merged, o, T, w->proj_w + (size_t)layer * D * D,
+    adapted_linear(m, w, 1, layer, ks, nk, merged, o, T, w->proj_w + (size_t)layer * D * D,
                    w->proj_b + (size_t)layer * D, y);
     for (size_t i = 0; i < (size_t)T * D; ++i) x[i] += y[i];
 
     ora_layernorm(x, T, D, w->ln2_g + (size_t)layer * D, w->ln2_b + (size_t)layer * D, m->ln_eps, u);
-    adapted_linear(m, w, 2, layer, k, merged, u, T, w->fc1_w + (size_t)layer * D * Dm,
+    adapted_linear(m, w, 2, layer, ks, nk, merged, u, T, w->fc1_w + (size_t)layer * D * Dm,
                    w->fc1_b + (size_t)layer * Dm, h);
     ora_gelu(h, (size_t)T * Dm);
-    adapted_linear(m, w, 3, layer, k, merged, h, T, w->fc2_w + (size_t)layer * Dm * D,
+    adapted_linear(m, w, 3, layer, ks, nk, merged, h, T, w->fc2_w + (size_t)layer * Dm * D,
                    w->fc2_b + (size_t)layer * D, y);
     for (size_t i = 0; i < (size_t)T * D; ++i) x[i] += y[i];
 
@@ -246,7 +259,7 @@ int ora_forward(const ora_model *m, const ora_weights *w, const float *frames, i
         double *x = trunk + (size_t)f * T * D;
         ora_patch_embed(frames + (size_t)f * m->H * m->W * 3, m->H, m->W, m->patch, D, w->patch_w, w->patch_b,
                         w->cls, w->pos, x);
-        for (int l = 0; l < m->L0 && l < m->L; ++l) block_layer(m, w, l, -1, 0, T, x);
+        for (int l = 0; l < m->L0 && l < m->L; ++l) block_layer(m, w, l, NULL, 0, 0, T, x);
     }
 
     int32_t *frame_of = (int32_t *)malloc(sizeof(int32_t) * (size_t)(R > 0 ? R : 1));
@@ -259,7 +272,7 @@ int ora_forward(const ora_model *m, const ora_weights *w, const float *frames, i
         double *x = (double *)malloc(sizeof(double) * (size_t)T * D);
         double *z = (double *)malloc(sizeof(double) * (size_t)D);
         memcpy(x, trunk + (size_t)frame_of[b] * T * D, sizeof(double) * (size_t)T * D);
-        for (int l = m->L0; l < m->L; ++l) block_layer(m, w, l, k, merged, T, x);
+        for (int l = m->L0; l < m->L; ++l) block_layer(m, w, l, &adapter_ids[b], 1, merged, T, x);
         if (x_final) memcpy(x_final + (size_t)b * T * D, x, sizeof(double) * (size_t)T * D);
         ora_layernorm(x, 1, D, w->lnf_g, w->lnf_b, m->ln_eps, z);
         ora_linear(z, 1, D, w->head_w + (size_t)k * D * C, w->head_b + (size_t)k * C, C, logits + (size_t)b * C);
@@ -279,6 +292,55 @@ int ora_forward(const ora_model *m, const ora_weights *w, const float *frames, i
             }
     }
     free(trunk); free(frame_of);
+    return 0;
+}
+
+/* The other reading of Sec. 3.1 for several active adapters: ONE hidden state per frame with all of the frame's
+ * adapters summed on top of the shared weights,
+ *     linear(x) = x W + b + sum_{k in S_f} s (x A_k) B_k        in layers [L0, L),
+ * and then every active adapter's own head on that one state: row b = (f, k) of the CSR arrays gets
+ *     logits[b] = LN(x_f[0]) H_k + hb_k,  scores[b] = sigmoid(logits[b]).
+ * Arguments and the optional merge to the label space as in ora_forward; x_final is [F][T][D]. */
+int ora_forward_sum(const ora_model *m, const ora_weights *w, const float *frames, int F,
+                    const int32_t *row_offsets, const int32_t *adapter_ids, int merged,
+                    double *logits, double *scores, double *merged_out, int K, double *x_final)
+{
+    const int T = 1 + (m->H / m->patch) * (m->W / m->patch), D = m->D, C = m->C;
+    const int R = row_offsets[F];
+    for (int f = 0; f < F; ++f) if (row_offsets[f + 1] < row_offsets[f]) return -1;
+    for (int b = 0; b < R; ++b) if (adapter_ids[b] < 0 || adapter_ids[b] >= m->n_adapters) return -1;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int f = 0; f < F; ++f) {
+        const int32_t *ks = adapter_ids + row_offsets[f];
+        const int nk = row_offsets[f + 1] - row_offsets[f];
+        double *x = (double *)malloc(sizeof(double) * (size_t)T * D);
+        double *z = (double *)malloc(sizeof(double) * (size_t)D);
+        ora_patch_embed(frames + (size_t)f * m->H * m->W * 3, m->H, m->W, m->patch, D, w->patch_w, w->patch_b,
+                        w->cls, w->pos, x);
+        for (int l = 0; l < m->L; ++l) block_layer(m, w, l, ks, l >= m->L0 ? nk : 0, merged, T, x);
+        if (x_final) memcpy(x_final + (size_t)f * T * D, x, sizeof(double) * (size_t)T * D);
+        ora_layernorm(x, 1, D, w->lnf_g, w->lnf_b, m->ln_eps, z);
+        for (int a = 0; a < nk; ++a) {
+            const int b = row_offsets[f] + a, k = ks[a];
+            ora_linear(z, 1, D, w->head_w + (size_t)k * D * C, w->head_b + (size_t)k * C, C, logits + (size_t)b * C);
+            for (int c = 0; c < C; ++c)
+                scores[(size_t)b * C + c] = 1.0 / (1.0 + exp(-logits[(size_t)b * C + c]));
+        }
+        free(x); free(z);
+    }
+
+    if (merged_out && w->class_map) {
+        for (size_t i = 0; i < (size_t)F * K; ++i) merged_out[i] = 0.0;
+        for (int f = 0; f < F; ++f)
+            for (int b = row_offsets[f]; b < row_offsets[f + 1]; ++b)
+                for (int c = 0; c < C; ++c) {
+                    const int cls = w->class_map[(size_t)adapter_ids[b] * C + c];
+                    if (cls < 0 || cls >= K) continue;
+                    double *dst = merged_out + (size_t)f * K + cls;
+                    if (scores[(size_t)b * C + c] > *dst) *dst = scores[(size_t)b * C + c];
+                }
+    }
     return 0;
 }
 

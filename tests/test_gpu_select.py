@@ -123,3 +123,25 @@ def test_invalid_arguments_are_refused_on_the_host():
     s = torch.zeros((1, 2000), device="cuda")
     m = torch.zeros((2, 2000), dtype=torch.uint8, device="cuda")
     assert binding.poly_select(s, m, z, z, z, check=False) == binding.POLY_EINVAL      # K above the limit
+
+
+@pytest.mark.parametrize("M_max", [45, 50])
+def test_tau_sweep_on_overlapping_contexts_built_from_co_occurrence(M_max):
+    """Overlapping contexts (Alg. 1 with overlap on a synthetic co-occurrence matrix, M = 45 / 50 contexts of up to 5 over 80
+    labels), an accuracy table a_{C,l} and the whole 1024-frame label stream in one stateful call: adapter sets, the count of
+    uncovered labels and the stream statistics at every tau, with and without context copy."""
+    cooc, _, _ = synth.make_cooccurrence(p_partner=0.5, seed=2003, shuffle=False)
+    mem, _ = oracle.build_contexts(cooc, 5, M_max, allow_overlap=True)
+    assert mem.shape == (M_max, 80) and mem.sum(0).max() > 1
+    acc = synth.make_accuracy_table(mem)
+    scores, _ = synth.make_label_stream(1024)
+    seen = set()
+    for tau in (0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9):
+        for copy in (False, True):
+            o_off, o_ids, o_unc = oracle.select(scores, mem, acc=acc, tau=tau, context_copy=copy, state=oracle.SelectState(80, M_max))
+            g_state = torch.zeros(binding.poly_select_state_bytes(80), dtype=torch.uint8, device="cuda")
+            off, ids, n, unc = gpu_select(scores, mem, acc=acc, tau=tau, context_copy=copy, state=g_state)
+            assert np.array_equal(off, o_off) and np.array_equal(ids, o_ids) and unc == o_unc and n == len(o_ids), (tau, copy)
+            assert binding.poly_stream_metrics(off, ids, M_max) == oracle.stream_metrics(o_off, o_ids, M_max)
+            seen.add((len(o_ids), o_unc))
+    assert len(seen) > 9                                  # tau and the copy branch both change the outcome on this stream

@@ -98,6 +98,44 @@ def test_lora_linear_matches_library_and_forward_linear():
     assert np.array_equal(oracle.lora_linear(case, s=2.0, b_begin=2, b_end=5), Y[2:5])
 
 
+# ------------------------------------------------- several adapters summed on one hidden state (Sec. 3.1)
+
+def test_sum_composition_with_one_adapter_per_frame_is_the_branch_reading():
+    cfg, w, frames, _, _ = _case(27, F=3, n_adapters=4, L=2)
+    off, ids = synth.sets_to_csr([[2], [], [0]])
+    a = oracle.forward(cfg, w, frames, off, ids, want_x=True, K=12)
+    b = oracle.forward(cfg, w, frames, off, ids, want_x=True, K=12, compose="sum")
+    assert np.array_equal(a["logits"], b["logits"]) and np.array_equal(a["merged"], b["merged"])
+    assert np.array_equal(a["x"][0], b["x"][0]) and np.array_equal(a["x"][1], b["x"][2])
+
+
+def test_sum_composition_equals_the_forward_with_all_deltas_merged():
+    cfg, w, frames, _, _ = _case(28, F=2, n_adapters=4, L=2)
+    off, ids = synth.sets_to_csr([[3, 1, 0], [2, 1]])
+    a = oracle.forward(cfg, w, frames, off, ids, compose="sum")
+    b = oracle.forward(cfg, w, frames, off, ids, compose="sum", merged=True)
+    assert 0 < np.abs(a["logits"] - b["logits"]).max() < 1e-6          # two different evaluation orders of the same sum
+    # and it is not the branch reading: the other adapters of the frame change a row
+    c = oracle.forward(cfg, w, frames, off, ids)
+    assert np.abs(a["logits"] - c["logits"]).max() > 1e-4
+
+
+def test_sum_composition_rows_share_the_frame_state_and_ignore_the_order_of_the_set():
+    cfg, w, frames, _, _ = _case(29, F=2, n_adapters=4, L=2, C=3)
+    off, ids = synth.sets_to_csr([[0, 2, 3], [1]])
+    a = oracle.forward(cfg, w, frames, off, ids, compose="sum", K=12)
+    off2, ids2 = synth.sets_to_csr([[3, 0, 2], [1]])
+    b = oracle.forward(cfg, w, frames, off2, ids2, compose="sum", K=12)
+    # same sets: the rows move with their adapters; sums of doubles in another order agree to rounding
+    assert np.abs(a["logits"][[0, 1, 2]] - b["logits"][[1, 2, 0]]).max() < 1e-12
+    assert np.abs(a["merged"] - b["merged"]).max() < 1e-12
+    # zero B: every row is the bare backbone read by its adapter's head
+    wz = {k: (np.zeros_like(v) if k.startswith("B_") else v) for k, v in w.items()}
+    z = oracle.forward(cfg, wz, frames, off, ids, compose="sum")
+    bare = oracle.forward(cfg, w, frames, off, ids, L0=cfg.L)
+    assert np.array_equal(z["logits"], bare["logits"])
+
+
 # ---------------------------------------------------------------- Table 2
 
 def _table2():

@@ -95,8 +95,12 @@ def test_patch_embed_matches_strided_convolution():
     assert np.abs(got - want).max() < 1e-12
 
 
-def _torch_forward(cfg, w, frame, k, L0):
-    """Whole forward of one (frame, adapter) branch from library routines, merged weights W + s A B."""
+def _torch_forward(cfg, w, frame, k, L0, head=None):
+    """Whole forward of one (frame, adapter) branch from library routines, merged weights W + s A B.  `k` may be a list of
+    adapters: then all of them are merged into the weights (W + s sum_k A_k B_k) and `head` names the adapter whose head reads
+    the result."""
+    ks = list(k) if isinstance(k, (list, tuple)) else [k]
+    k = ks[0] if head is None else head
     t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
     p, D, h = cfg.patch, cfg.D, cfg.heads
     cw = t(w["patch_w"]).reshape(p, p, 3, D).permute(3, 2, 0, 1)
@@ -107,7 +111,8 @@ def _torch_forward(cfg, w, frame, k, L0):
         W = t(w[f"{name}_w"][l])
         bit = dict(qkv=1, proj=2, fc1=4, fc2=8)[name]
         if l >= L0 and cfg.targets & bit:
-            W = W + cfg.lora_scale * t(w[f"A_{name}"][l, k]) @ t(w[f"B_{name}"][l, k])
+            for ka in ks:
+                W = W + cfg.lora_scale * t(w[f"A_{name}"][l, ka]) @ t(w[f"B_{name}"][l, ka])
         return W
 
     for l in range(cfg.L):
@@ -147,3 +152,23 @@ def test_config1_forward_matches_library_composition():
         for b in range(off[f], off[f + 1]):
             lg, sc, _ = _torch_forward(cfg, w, frames[f], int(ids[b]), 0)
             assert np.abs(out["logits"][b] - lg).max() < 1e-10
+
+
+@pytest.mark.parametrize("targets,L0", [(15, 0), (3, 1), (9, 2)])
+def test_sum_composition_matches_library_composition_with_summed_weights(targets, L0):
+    """Sec. 3.1, several adapters "summed on top": one state per frame equal to the forward whose weights are
+    W + s sum_k A_k B_k over the frame's set, read by each active adapter's own head."""
+    cfg, w, frames, _, _ = synth.make_small_case(70 + targets, targets=targets, L=3, F=3, n_adapters=4)
+    for n in list(w):
+        if n.startswith("B_"):
+            w[n] = w[n] * 10
+    off, ids = synth.sets_to_csr([[2, 0, 3], [], [1, 3]])
+    out = oracle.forward(cfg, w, frames, off, ids, L0=L0, want_x=True, compose="sum")
+    assert out["x"].shape[0] == 3
+    for f in range(3):
+        ks = [int(k) for k in ids[off[f]:off[f + 1]]]
+        for b in range(off[f], off[f + 1]):
+            lg, sc, x = _torch_forward(cfg, w, frames[f], ks, L0, head=int(ids[b]))
+            assert np.abs(out["x"][f] - x).max() < 1e-9
+            assert np.abs(out["logits"][b] - lg).max() < 1e-10
+            assert np.abs(out["scores"][b] - sc).max() < 1e-12

@@ -42,6 +42,11 @@ typedef enum poly_status {
 
 enum { POLY_F32 = 0, POLY_BF16 = 1 };
 enum { POLY_TGT_QKV = 1, POLY_TGT_PROJ = 2, POLY_TGT_FC1 = 4, POLY_TGT_FC2 = 8 };
+/* How a frame's several active adapters are applied (Sec. 3.1 / Fig. 3b leave both readings open):
+ *   POLY_COMPOSE_BRANCH  one branch per (frame, adapter): row-block (f, k) runs layers [L0, L) with adapter k alone;
+ *   POLY_COMPOSE_SUM     one hidden state per frame with all of its adapters summed on top of the shared weights,
+ *                        linear(x) = x W + b + sum_{k in S_f} lora_scale (x A_k) B_k, read by each active adapter's head. */
+enum { POLY_COMPOSE_BRANCH = 0, POLY_COMPOSE_SUM = 1 };
 
 /* Limits of this build. */
 enum {
@@ -130,6 +135,7 @@ typedef struct poly_model_desc {
     int32_t dtype;        /* POLY_F32 or POLY_BF16 */
     float lora_scale;     /* s */
     float ln_eps;
+    int32_t compose;      /* POLY_COMPOSE_BRANCH (0) or POLY_COMPOSE_SUM */
 } poly_model_desc;
 
 typedef struct poly_base_weights {

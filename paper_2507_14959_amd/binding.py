@@ -31,7 +31,7 @@ STAGES = ("select", "gemm", "shrink", "attention", "layernorm", "other")
 class ModelDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("H", "W", "patch", "D", "heads", "L", "Dm", "L0", "targets", "r",
                                          "n_adapters", "C", "dtype")] + \
-               [("lora_scale", C.c_float), ("ln_eps", C.c_float)]
+               [("lora_scale", C.c_float), ("ln_eps", C.c_float), ("compose", C.c_int32)]
 
 
 class BaseWeights(C.Structure):
@@ -148,7 +148,8 @@ class DeviceModel:
     matrices to the element type and uploads.
     """
 
-    def __init__(self, cfg, w: Dict[str, np.ndarray], L0: Optional[int] = None, device="cuda"):
+    def __init__(self, cfg, w: Dict[str, np.ndarray], L0: Optional[int] = None, device="cuda", compose: str = "branch"):
+        assert compose in ("branch", "sum")
         self.cfg = cfg
         self.L0 = cfg.L0 if L0 is None else L0
         elt = _elt(cfg.dtype)
@@ -173,7 +174,8 @@ class DeviceModel:
             self.t["class_map"] = torch.from_numpy(np.ascontiguousarray(w["class_map"], dtype=np.int32)).to(device)
 
         self.desc = ModelDesc(cfg.H, cfg.W, cfg.patch, cfg.D, cfg.heads, cfg.L, cfg.Dm, self.L0, cfg.targets, cfg.r,
-                              cfg.n_adapters, cfg.C, cfg.dtype, float(cfg.lora_scale), float(cfg.ln_eps))
+                              cfg.n_adapters, cfg.C, cfg.dtype, float(cfg.lora_scale), float(cfg.ln_eps),
+                              1 if compose == "sum" else 0)
         self.base = BaseWeights(**{n: self.t[n].data_ptr() for n, _ in BaseWeights._fields_})
         self.lora = LoraWeights()
         for i, n in enumerate(TARGETS):
@@ -357,7 +359,7 @@ def poly_profile_end() -> Dict[str, Dict[str, float]]:
 
 # --------------------------------------------------------------------------- conveniences for tests and the bench
 
-def run_forward(model: DeviceModel, frames_np: np.ndarray, row_offsets_np, adapter_ids_np, K: int = 0, R_cap: Optional[int] = None):
+def run_forward(model: "DeviceModel", frames_np: np.ndarray, row_offsets_np, adapter_ids_np, K: int = 0, R_cap: Optional[int] = None):
     """Allocate buffers, call poly_forward once, synchronise and return host arrays."""
     dev = "cuda"
     F = frames_np.shape[0]

@@ -56,6 +56,7 @@ int check_model(const poly_model_desc *m)
     if (m->L0 < 0 || m->L0 > m->L) return POLY_EINVAL;
     if (m->r <= 0 || m->r > POLY_MAX_RANK || m->n_adapters <= 0 || m->C <= 0 || m->C > POLY_MAX_HEAD_CLASSES) return POLY_EINVAL;
     if (m->targets & ~15) return POLY_EINVAL;
+    if (m->compose != POLY_COMPOSE_BRANCH && m->compose != POLY_COMPOSE_SUM) return POLY_EINVAL;
     const int T = 1 + (m->H / m->patch) * (m->W / m->patch);
     if (m->dtype == POLY_BF16) {
         // 16-byte vector loads along the contraction index; attention keeps a block's keys in LDS
@@ -127,6 +128,7 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
     const int RP = rank_pad(m->r);
     const size_t es = elt_size(dt);
     const int *R_dev = &w.meta->R;
+    const bool sum = m->compose == POLY_COMPOSE_SUM;
 
     // tokens: x[f][0] = cls + pos[0]; x[f][1 + t] = patch_t W_pe + b_pe + pos[1 + t].  The same launch checks the CSR arrays and
     // builds the row maps (nothing before the first adapted layer needs them).
@@ -160,14 +162,17 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
         if (l == m->L0 && !selected) POLY_TRY(select_now());
         const bool lora_on = l >= m->L0 && R > 0;
         if (l >= m->L0 && R == 0) break;
-        const bool fan = l == m->L0;           // first adapted layer: frames fan out into row-blocks
-        const bool branch = l > m->L0;         // residual stream already per row-block
+        // Summed composition: the frame stays ONE block through the adapted layers; its adapters' low-rank terms
+        // (one shrink per (frame, adapter) pair, as in the fan-out) are all added in the expand of the frame's block.
+        const bool summed = sum && l >= m->L0;
+        const bool fan = !sum && l == m->L0;   // first adapted layer: frames fan out into row-blocks
+        const bool branch = !sum && l > m->L0; // residual stream already per row-block
         float *x_in = branch ? w.xb : w.xa;
-        float *x_out = l >= m->L0 ? w.xb : w.xa;
+        float *x_out = (!sum && l >= m->L0) ? w.xb : w.xa;
         const int nb = branch ? R : F;         // blocks of the LayerNorm-1 input
-        const int *nb_dev = branch ? R_dev : nullptr;
-        const int n_out = l >= m->L0 ? R : F;  // blocks after the qkv linear
-        const int *n_out_dev = l >= m->L0 ? R_dev : nullptr;
+        const int *nb_dev = branch ? R_dev : (summed ? &w.meta->F_ok : nullptr);
+        const int n_out = (!sum && l >= m->L0) ? R : F;  // blocks after the qkv linear
+        const int *n_out_dev = (!sum && l >= m->L0) ? R_dev : (summed ? &w.meta->F_ok : nullptr);
 
         auto lora_ptr = [&](const void *stack, int t, size_t din, size_t dout, bool is_A) -> const void * {
             (void)t;
@@ -178,7 +183,15 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
 
         // narrow models (D <= 192, bf16): LayerNorm, shrink, base product and expand of one linear run in one
         // kernel that keeps 64 token rows on chip; otherwise LayerNorm / shrink / GEMM are separate launches
-        auto fused = [&](int t) { return dt == POLY_BF16 && rowlin_supported(D, t == 0 ? 3 * D : (t == 2 ? Dm : D), m->r, use(t), t == 1); };
+        auto fused = [&](int t) { return dt == POLY_BF16 && !(summed && use(t)) && rowlin_supported(D, t == 0 ? 3 * D : (t == 2 ? Dm : D), m->r, use(t), t == 1); };
+        // low-rank operands of the GEMM path: S block and adapter per (frame, adapter) pair; summed: the pairs of a frame
+        // all land on the frame's block
+        const int *shrink_map = summed ? w.frame_of_row : nullptr;
+        auto lora_gemm = [&](GemmArgs &g, int t, const void *Bt) {
+            g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = m->r; g.adapter_of_out = w.adapter_of_row;
+            g.set_off = summed ? row_offsets : nullptr;
+            (void)t;
+        };
         auto rowlin = [&](int t, const float *x_ln, const float *ln_g, const float *ln_b, const void *a_in, const int *in_map,
                           const void *Wt, const float *bias, int N, int mode, void *out, const float *res, const int *res_map) -> int {
             RowLinArgs a = {};
@@ -210,8 +223,8 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
             g.out_off = fan ? row_offsets : nullptr;
             if (use(0)) {
                 const void *At = lora_ptr(lora->At[0], 0, D, 3 * D, true), *Bt = lora_ptr(lora->Bt[0], 0, D, 3 * D, false);
-                POLY_TRY(launch_shrink(w.u, T, D, At, m->r, RP, m->lora_scale, R, R_dev, fan_map, w.adapter_of_row, w.S, dt, st));
-                g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = m->r; g.adapter_of_out = w.adapter_of_row;
+                POLY_TRY(launch_shrink(w.u, T, D, At, m->r, RP, m->lora_scale, R, R_dev, summed ? shrink_map : fan_map, w.adapter_of_row, w.S, dt, st));
+                lora_gemm(g, 0, Bt);
             }
             g.mode = EPI_STORE; g.out = w.qkv; g.Tout = T;
             POLY_TRY(launch_gemm(g, dt, st));
@@ -219,10 +232,10 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
         POLY_TRY(launch_attention(w.qkv, w.o, T, D, m->heads, n_out, n_out_dev, dt, st));
         // narrow models without adapters on fc1 / fc2: everything row-wise of the layer in one launch -- proj with its
         // residual, the MLP half, and the qkv linear of the next layer when that layer works on the same blocks
-        if (dt == POLY_BF16 && !use(2) && !use(3) && rowlayer_supported(D, Dm, (use(0) || use(1)) ? m->r : 0)) {
+        if (dt == POLY_BF16 && !use(2) && !use(3) && !(summed && (use(0) || use(1))) && rowlayer_supported(D, Dm, (use(0) || use(1)) ? m->r : 0)) {
             RowLayerArgs a = {};
             a.T = T; a.D = D; a.Dm = Dm; a.n_out = n_out; a.n_out_dev = n_out_dev;
-            a.adapter_of_out = lora_on ? w.adapter_of_row : nullptr; a.r = m->r; a.scale = m->lora_scale; a.eps = m->ln_eps;
+            a.adapter_of_out = (lora_on && !sum) ? w.adapter_of_row : nullptr; a.r = m->r; a.scale = m->lora_scale; a.eps = m->ln_eps;
             a.o = (const bf16_t *)w.o; a.Wpt = (const bf16_t *)Wproj; a.bp = base->proj_b + (size_t)l * D;
             if (use(1)) { a.Apt = (const bf16_t *)lora_ptr(lora->At[1], 1, D, D, true); a.Bpt = (const bf16_t *)lora_ptr(lora->Bt[1], 1, D, D, false); }
             a.res = x_in; a.res_block_of_out = fan_map;
@@ -231,10 +244,11 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
             a.W2t = (const bf16_t *)((const char *)base->fc2_w + es * (size_t)l * D * Dm); a.b2 = base->fc2_b + (size_t)l * D;
             a.x_out = x_out;
             const int ln = l + 1;              // next layer: same blocks unless it is the one where frames fan out
-            if (ln < m->L && ln != m->L0) {
+            const bool next_qkv_summed = sum && ln >= m->L0 && R > 0 && (m->targets & 1);   // that linear needs the GEMM path
+            if (ln < m->L && (sum || ln != m->L0) && !next_qkv_summed) {
                 a.lnq_g = base->ln1_g + (size_t)ln * D; a.lnq_b = base->ln1_b + (size_t)ln * D;
                 a.Wqt = (const bf16_t *)((const char *)base->qkv_w + es * (size_t)ln * 3 * D * D); a.bq = base->qkv_b + (size_t)ln * 3 * D;
-                if (ln >= m->L0 && R > 0 && (m->targets & 1)) {
+                if (!sum && ln >= m->L0 && R > 0 && (m->targets & 1)) {
                     const size_t per_layer = (size_t)m->n_adapters * m->r * D;
                     a.Aqt = (const bf16_t *)((const char *)lora->At[0] + es * per_layer * (size_t)(ln - m->L0));
                     a.Bqt = (const bf16_t *)((const char *)lora->Bt[0] + es * per_layer * 3 * (size_t)(ln - m->L0));
@@ -253,8 +267,8 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
             g.T = T; g.K = D; g.N = D; g.n_in = n_out; g.n_in_dev = n_out_dev;
             if (use(1)) {
                 const void *At = lora_ptr(lora->At[1], 1, D, D, true), *Bt = lora_ptr(lora->Bt[1], 1, D, D, false);
-                POLY_TRY(launch_shrink(w.o, T, D, At, m->r, RP, m->lora_scale, R, R_dev, nullptr, w.adapter_of_row, w.S, dt, st));
-                g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = m->r; g.adapter_of_out = w.adapter_of_row;
+                POLY_TRY(launch_shrink(w.o, T, D, At, m->r, RP, m->lora_scale, R, R_dev, shrink_map, w.adapter_of_row, w.S, dt, st));
+                lora_gemm(g, 1, Bt);
             }
             g.mode = EPI_RESID; g.out = x_out; g.Tout = T; g.res = x_in; g.res_block_of_out = fan_map;
             POLY_TRY(launch_gemm(g, dt, st));
@@ -280,8 +294,8 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
             g.T = T; g.K = D; g.N = Dm; g.n_in = n_out; g.n_in_dev = n_out_dev;
             if (use(2)) {
                 const void *At = lora_ptr(lora->At[2], 2, D, Dm, true), *Bt = lora_ptr(lora->Bt[2], 2, D, Dm, false);
-                POLY_TRY(launch_shrink(w.u, T, D, At, m->r, RP, m->lora_scale, R, R_dev, nullptr, w.adapter_of_row, w.S, dt, st));
-                g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = m->r; g.adapter_of_out = w.adapter_of_row;
+                POLY_TRY(launch_shrink(w.u, T, D, At, m->r, RP, m->lora_scale, R, R_dev, shrink_map, w.adapter_of_row, w.S, dt, st));
+                lora_gemm(g, 2, Bt);
             }
             g.mode = EPI_GELU; g.out = w.h; g.Tout = T;
             POLY_TRY(launch_gemm(g, dt, st));
@@ -292,8 +306,8 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
             g.T = T; g.K = Dm; g.N = D; g.n_in = n_out; g.n_in_dev = n_out_dev;
             if (use(3)) {
                 const void *At = lora_ptr(lora->At[3], 3, Dm, D, true), *Bt = lora_ptr(lora->Bt[3], 3, Dm, D, false);
-                POLY_TRY(launch_shrink(w.h, T, Dm, At, m->r, RP, m->lora_scale, R, R_dev, nullptr, w.adapter_of_row, w.S, dt, st));
-                g.S = w.S; g.RP = RP; g.Bt = Bt; g.r = m->r; g.adapter_of_out = w.adapter_of_row;
+                POLY_TRY(launch_shrink(w.h, T, Dm, At, m->r, RP, m->lora_scale, R, R_dev, shrink_map, w.adapter_of_row, w.S, dt, st));
+                lora_gemm(g, 3, Bt);
             }
             g.mode = EPI_RESID; g.out = x_out; g.Tout = T; g.res = x_out;
             POLY_TRY(launch_gemm(g, dt, st));
@@ -302,7 +316,7 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
 
     if (!selected) POLY_TRY(select_now());        // (L0 == L: the shared layers are the whole backbone)
     if (R > 0) {
-        POLY_TRY(launch_head(adapted ? w.xb : w.xa, adapted ? nullptr : w.frame_of_row, T, D, base->lnf_g, base->lnf_b, m->ln_eps,
+        POLY_TRY(launch_head((adapted && !sum) ? w.xb : w.xa, (adapted && !sum) ? nullptr : w.frame_of_row, T, D, base->lnf_g, base->lnf_b, m->ln_eps,
                              heads->head_w, heads->head_b, m->C, w.adapter_of_row, w.frame_of_row, heads->class_map, K, w.meta, R,
                              out_logits, out_scores, out_merged, dt, st));
     }

@@ -133,10 +133,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_generic_kernel(const GemmArgs g
 #pragma unroll
             for (int j = 0; j < NJ; ++j) c[i][j] = acc[i][j];
 
-        const int k_ad = (g.S && g.adapter_of_out) ? g.adapter_of_out[ob] : -1;
-        if (k_ad >= 0) {
+        const bool has_lora = g.S && g.adapter_of_out;
+        const int sb0 = g.set_off ? g.set_off[ob] : ob, sb1 = g.set_off ? g.set_off[ob + 1] : ob + 1;
+        for (int sb = sb0; has_lora && sb < sb1; ++sb) {
+            const int k_ad = g.adapter_of_out[sb];
+            if (k_ad < 0) continue;
             // expand: one more K step per 16 ranks; A operand = S rows, B operand = Bt_k rows
-            const bf16_t *S = (const bf16_t *)g.S + (size_t)ob * g.T * g.RP;
+            const bf16_t *S = (const bf16_t *)g.S + (size_t)sb * g.T * g.RP;
             const bf16_t *Bt = (const bf16_t *)g.Bt + (size_t)k_ad * g.N * g.r;
             for (int s0 = 0; s0 < g.RP; s0 += 16) {
                 const int j0 = s0 + lh * 8;
@@ -345,7 +348,7 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
     const bool has_lora = g.S && g.adapter_of_out;
     bf16x8 fs0[MI], fw0[NJ];
     int k_ad0 = -1;
-    if (EARLY && has_lora && !flat) {
+    if (EARLY && has_lora && !flat && !g.set_off) {
         k_ad0 = g.adapter_of_out[ob0];
         if (k_ad0 >= 0) { load_fs(fs0, ob0, 0); load_fw(fw0, k_ad0, 0); }
     }
@@ -451,15 +454,17 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
                 const int hi = min(32, g.Tb - trow0);                       // rows [lo, hi) of the subtile belong to block bb
                 const int o0 = g.out_off ? g.out_off[bb] : bb, o1 = g.out_off ? g.out_off[bb + 1] : bb + 1;
                 for (int ob = o0; ob < o1; ++ob) {
-                    const int k_ad = has_lora ? g.adapter_of_out[ob] : -1;
                     const int rb = (g.mode == EPI_RESID && g.res) ? (g.res_block_of_out ? g.res_block_of_out[ob] : ob) : 0;
                     f32x16 c[NJ];
 #pragma unroll
                     for (int j = 0; j < NJ; ++j) c[j] = acc[i][j];
-                    if (k_ad >= 0) {
+                    const int sb0 = g.set_off ? g.set_off[ob] : ob, sb1 = g.set_off ? g.set_off[ob + 1] : ob + 1;
+                    for (int sb = sb0; has_lora && sb < sb1; ++sb) {     // one low-rank term, or all the terms summed on this block
+                        const int k_ad = g.adapter_of_out[sb];
+                        if (k_ad < 0) continue;
                         const int t = min(max(trow0 + lm, 0), g.Tb - 1);
                         for (int s0 = 0; s0 < g.RP; s0 += 16) {
-                            bf16x8 fsb = *(const bf16x8 *)((const bf16_t *)g.S + ((size_t)ob * g.Tb + t) * g.RP + s0 + lh * 8);
+                            bf16x8 fsb = *(const bf16x8 *)((const bf16_t *)g.S + ((size_t)sb * g.Tb + t) * g.RP + s0 + lh * 8);
                             if (lm < lo || lm >= hi) fsb = zero8;
                             bf16x8 fwb[NJ];
                             load_fw(fwb, k_ad, s0);
@@ -470,6 +475,36 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
                     emit(c, ob, rb, trow0, lo, hi);
                 }
                 lo = hi;
+            }
+        }
+        return;
+    }
+
+    if (g.set_off) {
+        // several low-rank terms summed on one output block: operands fetched term by term, one subtile at a time
+        for (int ob = ob0; ob < ob1; ++ob) {
+            const int rb = (g.mode == EPI_RESID && g.res) ? (g.res_block_of_out ? g.res_block_of_out[ob] : ob) : 0;
+            const int sb0 = g.set_off[ob], sb1 = g.set_off[ob + 1];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                const int tw = t0 + wm * MI * 32 + i * 32;
+                if (tw >= g.T) break;
+                f32x16 c[NJ];
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) c[j] = acc[i][j];
+                for (int sb = sb0; has_lora && sb < sb1; ++sb) {
+                    const int k_ad = g.adapter_of_out[sb];
+                    if (k_ad < 0) continue;
+                    const int t = min(tw + lm, g.T - 1);
+                    for (int s0 = 0; s0 < g.RP; s0 += 16) {
+                        const bf16x8 fsb = *(const bf16x8 *)((const bf16_t *)g.S + ((size_t)sb * g.T + t) * g.RP + s0 + lh * 8);
+                        bf16x8 fwb[NJ];
+                        load_fw(fwb, k_ad, s0);
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwb[j], fsb, c[j], 0, 0, 0);
+                    }
+                }
+                emit(c, ob, rb, tw, 0, min(32, g.T - tw));
             }
         }
         return;
@@ -559,7 +594,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g)
     }
 
     for (int ob = ob0; ob < ob1; ++ob) {
-        const int k_ad = (g.S && g.adapter_of_out) ? g.adapter_of_out[ob] : -1;
+        const bool has_lora = g.S && g.adapter_of_out;
+        const int sb0 = g.set_off ? g.set_off[ob] : ob, sb1 = g.set_off ? g.set_off[ob + 1] : ob + 1;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int t = t0 + ty * 4 + i;
@@ -569,8 +605,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g)
                 const int col = n0 + tx * 4 + j;
                 if (col >= g.N) continue;
                 float v = acc[i][j];
-                if (k_ad >= 0) {
-                    const float *S = (const float *)g.S + ((size_t)ob * g.T + t) * g.RP;
+                for (int sb = sb0; has_lora && sb < sb1; ++sb) {
+                    const int k_ad = g.adapter_of_out[sb];
+                    if (k_ad < 0) continue;
+                    const float *S = (const float *)g.S + ((size_t)sb * g.T + t) * g.RP;
                     const float *Bt = (const float *)g.Bt + ((size_t)k_ad * g.N + col) * g.r;
                     float d = 0.f;
                     for (int q = 0; q < g.r; ++q) d = fmaf(S[q], Bt[q], d);

@@ -153,6 +153,9 @@ struct GemmArgs {
     const void *Bt;       // elt [n_adapters][N][r]
     int r;
     const int *adapter_of_out;  // [n_out], < 0 = no adapter
+    const int *set_off;   // null: output block ob has the one low-rank term (S[ob], adapter_of_out[ob]).  Else [n_out+1]: output block
+                          // ob sums the terms (S[sb], adapter_of_out[sb]) for sb in [set_off[ob], set_off[ob+1]) -- several adapters
+                          // on one hidden state; S and adapter_of_out are then indexed by sb
     int mode;             // EPI_*
     void *out;            // EPI_STORE / EPI_GELU: elt [n_out*Tout][N]; EPI_RESID: float, same shape
     int Tout, t_off;      // output row of (ob, t) is ob*Tout + t_off + t

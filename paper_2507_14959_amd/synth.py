@@ -250,6 +250,28 @@ def make_lora_linear_case(n_xblocks: int = 256, T: int = 197, Kdim: int = 768, N
                 T=T, Kdim=Kdim, Ndim=Ndim, n_adapters=n_adapters, r=r, dtype=dtype)
 
 
+def make_paper_preset(F: int = 32, seed: int = 1006, adapters_per_frame: int | None = None):
+    """The setting the paper trains (Sec. 4): DeiT-tiny, 11 contexts with 5-class heads, rank 16 with scaling factor 32
+    (s = 32 / 16 = 2) on the query and value projections only, adapters on the last 20 % of the layers.
+
+    On the fused qkv linear D -> 3D a query + value adapter is ONE adapter of rank 32: A = [A_q | A_v] and
+    B = [[B_q, 0, 0], [0, 0, B_v]] (the key columns and the cross blocks of B are zero).  Returns (cfg, weights, frames,
+    row_offsets, adapter_ids) with 1 + Binomial(2, 0.4) adapters per frame (or exactly `adapters_per_frame`).
+    """
+    D, r = 192, 16
+    cfg = ModelCfg("deit-tiny-paper-preset", 224, 224, 16, D, 3, 12, 768, 11, 2 * r, TGT_QKV, 5, DT_BF16, L0=10, lora_scale=2.0)
+    rng = np.random.default_rng(seed)
+    w = make_weights(cfg, rng)
+    B = np.zeros_like(w["B_qkv"])                       # [L, N_ad, 2r, 3D]
+    B[:, :, :r, :D] = w["B_qkv"][:, :, :r, :D]          # query ranks write query columns
+    B[:, :, r:, 2 * D:] = w["B_qkv"][:, :, r:, 2 * D:]  # value ranks write value columns
+    w["B_qkv"] = B
+    frames = make_frames(cfg, F, rng)
+    sets = [_draw_ids(rng, cfg.n_adapters, adapters_per_frame or 1 + int(rng.binomial(2, 0.4)), None) for _ in range(F)]
+    off, ids = sets_to_csr(sets)
+    return cfg, w, frames, off, ids
+
+
 # ----------------------------------------------------------------------------
 # label stream (config 4)
 # ----------------------------------------------------------------------------

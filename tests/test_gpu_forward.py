@@ -18,10 +18,10 @@ pytestmark = pytest.mark.gpu
 TOL = {synth.DT_F32: 1e-4, synth.DT_BF16: 2e-2}
 
 
-def compare(cfg, w, frames, off, ids, L0, K=0):
-    model = binding.DeviceModel(cfg, w, L0=L0)
+def compare(cfg, w, frames, off, ids, L0, K=0, compose="branch"):
+    model = binding.DeviceModel(cfg, w, L0=L0, compose=compose)
     got = binding.run_forward(model, frames, off, ids, K=K)
-    want = oracle.forward(cfg, w, frames, off, ids, L0=L0, K=K)
+    want = oracle.forward(cfg, w, frames, off, ids, L0=L0, K=K, compose=compose)
     assert got["status"] == 0
     err = np.abs(got["logits"] - want["logits"]).max() if off[-1] else 0.0
     assert err < TOL[cfg.dtype], f"logits max-abs error {err}"
@@ -219,3 +219,50 @@ def test_rank_outside_the_row_layer_kernel_takes_the_single_linear_and_mlp_kerne
                                                       D=192, heads=3, Dm=768, hw=72, patch=8)     # T = 82: a full and a ragged tile
     compare(cfg, w, frames, off, ids, 0, K=cfg.n_adapters * cfg.C)
     compare(cfg, w, frames, off, ids, 2, K=cfg.n_adapters * cfg.C)
+
+
+# ------------------------------------------------- several adapters summed on one hidden state per frame (Sec. 3.1)
+
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
+@pytest.mark.parametrize("targets,L0,r", [(15, 0, 4), (3, 1, 8), (12, 0, 16), (5, 2, 4), (10, 3, 20)])
+def test_sum_composition_small_models_all_target_sets(dtype, targets, L0, r):
+    cfg, w, frames, _, _ = synth.make_small_case(240 + targets, dtype=dtype, targets=targets, L=3, F=5, r=r, max_set=3,
+                                                  n_adapters=4, hw=48, patch=8)   # T = 37; L0 = 3: no adapted layer at all
+    off, ids = synth.sets_to_csr([[0, 2, 3], [], [1, 3], [2], [3, 1, 0]])
+    _, want, _ = compare(cfg, w, frames, off, ids, L0, K=cfg.n_adapters * cfg.C, compose="sum")
+    if L0 < cfg.L:
+        branch = oracle.forward(cfg, w, frames, off, ids, L0=L0)
+        assert np.abs(branch["logits"] - want["logits"]).max() > 2 * TOL[dtype]     # the two readings differ visibly here
+
+
+@pytest.mark.parametrize("D,heads,Dm,hw,r,targets,L0", [
+    (192, 3, 768, 72, 8, 3, 2),      # DeiT-tiny widths, T = 82: shared layers in the row kernels, adapted ones on the GEMM path
+    (192, 3, 768, 72, 16, 1, 0),     # adapters on qkv only: proj + MLP of an adapted layer stay in the row kernel
+    (256, 4, 1024, 72, 16, 15, 1),   # wide path throughout
+    (768, 12, 1024, 64, 16, 15, 0),  # ViT-base width: the large GEMM tiles with summed terms
+])
+def test_sum_composition_bf16_widths(D, heads, Dm, hw, r, targets, L0):
+    cfg, w, frames, off, ids = synth.make_small_case(260 + D + r, dtype=synth.DT_BF16, targets=targets, L=4, F=6, r=r, max_set=3,
+                                                      n_adapters=5, D=D, heads=heads, Dm=Dm, hw=hw, patch=8)
+    compare(cfg, w, frames, off, ids, L0, K=cfg.n_adapters * cfg.C, compose="sum")
+
+
+def test_sum_composition_one_adapter_per_frame_is_the_branch_result_and_bad_ids_write_nothing():
+    cfg, w, frames, _, _ = synth.make_small_case(270, dtype=synth.DT_BF16, F=4, targets=15, n_adapters=4, D=256, heads=4, Dm=512, hw=40, patch=8)
+    off, ids = synth.sets_to_csr([[1], [], [3], [0]])
+    a = binding.run_forward(binding.DeviceModel(cfg, w), frames, off, ids)
+    b = binding.run_forward(binding.DeviceModel(cfg, w, compose="sum"), frames, off, ids)
+    assert np.array_equal(a["logits"], b["logits"])      # same kernels, same operands, same order
+    bad = ids.copy(); bad[1] = cfg.n_adapters
+    c = binding.run_forward(binding.DeviceModel(cfg, w, compose="sum"), frames, off, bad)
+    assert c["status"] == binding.POLY_ERANGE and np.all(np.isnan(c["logits"]))
+
+
+@pytest.mark.parametrize("compose", ["branch", "sum"])
+def test_paper_preset_query_value_rank16_scale2_last_two_layers(compose):
+    """Sec. 4: rank 16, scaling factor 32 (s = 2), query + value only, adapters on the last 20 % of the layers, 11 contexts."""
+    cfg, w, frames, off, ids = synth.make_paper_preset(F=8)
+    assert cfg.L0 == cfg.polymorph_L0() == 10 and cfg.lora_scale == 2.0
+    _, want, err = compare(cfg, w, frames, off, ids, cfg.L0, K=cfg.n_adapters * cfg.C, compose=compose)
+    # the key columns of the qkv adapter are silent: the same weights with only the query and value blocks kept
+    print(f"paper preset ({compose}): R={off[-1]}, logits max-abs error {err:.2e}")

@@ -40,7 +40,7 @@ def test_workspace_size_grows_with_rows_and_rejects_bad_models():
     import ctypes as C
     cfg = synth.CFG2
     d = binding.ModelDesc(cfg.H, cfg.W, cfg.patch, cfg.D, cfg.heads, cfg.L, cfg.Dm, 0, cfg.targets, cfg.r, cfg.n_adapters,
-                          cfg.C, cfg.dtype, 1.0, 1e-6)
+                          cfg.C, cfg.dtype, 1.0, 1e-6, 0)
     f = binding.lib().poly_forward_workspace_bytes
     a, b = f(C.byref(d), 32, 58), f(C.byref(d), 32, 96)
     assert 0 < a < b

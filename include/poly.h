@@ -5,8 +5,10 @@
  * Conventions
  *   - Plain C ABI.  Every tensor pointer is a DEVICE pointer unless it says "host".
  *     The structs themselves (poly_model_desc, poly_base_weights, ...) live in host memory.
- *   - The caller owns every buffer.  The library allocates nothing and keeps no state
- *     between calls; scratch memory comes in through `workspace`.
+ *   - The caller owns every buffer.  The entry points of this header allocate no device or
+ *     host memory and keep no state between calls; scratch memory comes in through
+ *     `workspace` (poly_lora_linear_static: the library's own static array).  The measurement
+ *     hooks in poly_profile.h are outside this contract.
  *   - Every call is asynchronous on `stream` (a hipStream_t passed as void*; NULL = the
  *     default stream).  Outputs are valid once the stream has been synchronised.
  *   - Return value: POLY_OK or a negative poly_status.  Conditions that only the device can
@@ -61,8 +63,7 @@ const char *poly_status_string(int status);
 
 /* ------------------------------------------------------------------------------------------
  * poly_select -- context detection for a batch of consecutive frames of one stream
- * (Alg. 2 "Greedy Context Detection with Conditional Context Copy", Sec. 3.5; the cover
- * constraint is Eq. 2).
+ * (Alg. 2, Sec. 3.5; the cover constraint is Eq. 2).
  *
  *   Y_t = { l : label_scores[t][l] >= theta }                     (the monitor of Sec. 3.2)
  *   Y_t == Y_{t-1}                                    -> S_t = S_{t-1}
@@ -122,6 +123,11 @@ int poly_select(const float *label_scores, int F, int K, const uint8_t *group_me
  *   workspace     >= poly_forward_workspace_bytes(m, F, R) bytes, 256-byte aligned.
  * Rows past row_offsets[F] are left untouched.  Results do not depend on where a frame sits in
  * the batch (fixed reduction order, no atomics on floating-point sums).
+ * Shape limits (POLY_EINVAL otherwise): D == 64 * heads; 1 <= r <= 64; 1 <= C <= 64; H, W multiples of patch;
+ * POLY_BF16: T = 1 + (H/patch)(W/patch) <= 224 tokens (a block's keys stay on chip), Dm % 8 == 0 and
+ * (3 * patch * patch) % 8 == 0 (16-byte loads along the contraction index); POLY_F32: both % 4 == 0.
+ * With POLY_COMPOSE_SUM the rows of out_logits / out_scores are the same (frame, adapter) pairs in CSR order, each
+ * adapter's head reading its frame's one hidden state.
  */
 typedef struct poly_model_desc {
     int32_t H, W, patch;  /* frame size and patch edge; H, W multiples of patch */
@@ -287,33 +293,6 @@ int poly_lora_linear_static(const void *X, int n_xblocks, int T, int Kdim, const
                             int Ndim, const void *At, const void *Bt, int n_adapters, int r, float scale,
                             const int32_t *row_offsets, const int32_t *adapter_ids, int R, void *Y, int dtype,
                             int32_t *dev_status, void *stream);
-
-/* ------------------------------------------------------------------------------------------
- * Per-stage kernel timing for measurement harnesses (not part of the method).  Between
- * poly_profile_begin and poly_profile_end every kernel the library launches carries a start/stop
- * event pair stamped by the runtime with the dispatch's own begin and end, and poly_profile_end
- * (which synchronises the device) returns, per stage, the number of launches and the sum of their
- * execution times in milliseconds.  `max_launches` bounds the number of recorded launches (host
- * events are created for them); launches beyond it run untimed.  Process-wide, not thread-safe.
- */
-enum {
-    POLY_STAGE_SELECT = 0, /* Alg. 2 kernel */
-    POLY_STAGE_GEMM = 1,   /* base linears with fused expand and epilogue (patch embedding included) */
-    POLY_STAGE_SHRINK = 2, /* x A_k */
-    POLY_STAGE_ATTN = 3,
-    POLY_STAGE_NORM = 4,   /* LayerNorm */
-    POLY_STAGE_OTHER = 5,  /* CSR check, patch gathering, class token, heads, merge */
-    POLY_STAGE_COUNT = 6
-};
-
-typedef struct poly_profile {
-    int32_t launches[POLY_STAGE_COUNT];
-    float ms[POLY_STAGE_COUNT];
-    int32_t dropped; /* recorded launches whose events could not be read */
-} poly_profile;
-
-int poly_profile_begin(int max_launches);
-int poly_profile_end(poly_profile *out); /* host struct */
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         s = os.path.join(CSRC, src)
         o = os.path.join(HERE, "_build", os.path.splitext(src)[0] + ".o")
         objs.append(o)
-        deps = [s, os.path.join(CSRC, "poly_dev.h"), os.path.join(CSRC, "rowtile.h"), os.path.join(HERE, "..", "include", "poly.h")]
+        deps = [s, os.path.join(CSRC, "poly_dev.h"), os.path.join(CSRC, "rowtile.h"), os.path.join(HERE, "..", "include", "poly.h"), os.path.join(HERE, "..", "include", "poly_profile.h")]
         if not force and os.path.exists(o) and all(os.path.getmtime(o) >= os.path.getmtime(d) for d in deps):
             continue
         if src.endswith(".cpp"):   # host-only source

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "../../include/poly.h"
+#include "../../include/poly_profile.h"
 
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));

@@ -10,9 +10,12 @@ LIB = os.path.join(ROOT, "paper_2507_14959_amd", "libpoly.so")
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "poly.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(poly_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in ("poly.h", "poly_profile.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(poly_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_entry_points():

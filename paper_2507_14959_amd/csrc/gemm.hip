@@ -239,8 +239,11 @@ __device__ __forceinline__ bool xcd_tile(int bid, int tiles_mtot, int tiles_n, i
     return true;
 }
 
-// BM x BN tile, WM x WN waves, each wave (BM/WM) x (BN/WN) = (MI*32) x (NJ*32); NS LDS stages of 64 k-columns
-template <int BM, int BN, int WM, int WN, int NS>
+// BM x BN tile, WM x WN waves, each wave (BM/WM) x (BN/WN) = (MI*32) x (NJ*32); NS LDS stages of 64 k-columns.
+// EK, the epilogue: 0 = subtile by subtile (fp32 output with residual / position rows, or one column subtile per wave);
+// 1, 2 = row-wise for bf16 output (two column subtiles per wave): 2 when the host knows that a wave's region touches at most two
+// input blocks and every output block has one low-rank term of at most 16 ranks (all operands of a pass prefetched), 1 otherwise.
+template <int BM, int BN, int WM, int WN, int NS, int EK>
 __global__ __launch_bounds__(64 * WM * WN, (BM * BN >= 256 * 256 || NS * (BM + BN) * 128 > 80 * 1024) ? 1 : 2)
 void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
 {
@@ -286,6 +289,22 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
         for (int i = 0; i < BG; ++i) POLY_GLDS16(Wt + gb[i] + kt * BK, st + A_EL + (wave * BG + i) * 512);
     };
 
+    // Row-wise epilogue (two column subtiles per wave, bf16 output): the accumulators start from the bias, so no output block
+    // has to add it later.  These loads go out before the tile loads: the in-order load counter then never makes their first
+    // use wait for a tile.
+    constexpr bool RW = EK > 0;
+    static_assert(!RW || NJ == 2, "row-wise epilogue: two column subtiles per wave");
+    constexpr bool rowwise = RW;
+    f32x4 bias_q[NJ][4];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int bcol = n0 + wn * NJ * 32 + j * 32 + 8 * q + 4 * lh;
+            const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
+            bias_q[j][q] = (rowwise && g.bias && bcol < g.N) ? *(const f32x4 *)(g.bias + bcol) : z4;
+        }
+
     // The tile loads need nothing but the tile coordinates, so they go out first; the row count, the fan-out
     // offsets and the adapter id are read while they fly.  A tile that turns out to be past the true row count
     // still read inside the caller's buffers (sized for the row bound); it drains its loads and leaves.
@@ -308,7 +327,7 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = bias_q[j][e >> 2][e & 3];
 
     // operands of the low-rank expand for ranks [s0, s0 + 16) of output block ob: S rows of this wave's MI row
     // subtiles and Bt rows of its NJ column subtiles (rows past T / columns past N are clamped or zero: they only
@@ -353,6 +372,41 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
         if (k_ad0 >= 0) { load_fs(fs0, ob0, 0); load_fw(fw0, k_ad0, 0); }
     }
 
+    // Row-wise epilogue: which input blocks this wave's (MI * 32)-row region touches, their fan-out and the adapters of the first
+    // two passes.  Every one of these is a chain of dependent loads and each link a full memory round trip under load, so the
+    // fan-out offsets are requested here, the adapter ids inside the main loop once the offsets have arrived, and nothing is
+    // waited for before the loop has run.
+    constexpr int RROWS = MI * 32, RCOLS = NJ * 32;
+    static_assert(!RW || NW * RROWS * RCOLS <= NS * STAGE_EL, "bf16 staging must fit in the tile ring");
+    int R0 = 0, Rend = 0, Tblk = 1, bbA = 0, bbZ = 0, baseA = 0, tB = 0, oA0 = 0, oA1 = 0, oB0 = 0, oB1 = 0, maxfan = 0;
+    int oA0v = 0, oA1v = 0, oB0v = 0, oB1v = 0;               // as loaded (per lane, all lanes equal)
+    int kA = -1, kB = -1, kAv = -1, kBv = -1, kAnv = -1, kBnv = -1;   // adapters of the current pass; as loaded: current / next pass
+    bool two = true, hasB = false;
+    if constexpr (RW) {
+        R0 = t0 + wm * RROWS; Rend = min(R0 + RROWS, Tlim);
+        if (R0 < Rend) {
+            Tblk = flat ? g.Tb : g.T;                         // rows of a block: stride of S and of the output blocks
+            bbA = flat ? R0 / Tblk : xb; bbZ = flat ? (Rend - 1) / Tblk : xb;
+            baseA = flat ? bbA * Tblk : 0; tB = baseA + Tblk;  // first row (tile coordinates) of blocks bbA and bbA + 1
+            two = bbZ - bbA <= 1; hasB = bbZ > bbA;
+            // fan-out of the region's first and last input block (with more than two blocks: looked up per block in the epilogue)
+            oA0v = g.out_off ? g.out_off[bbA] : bbA; oA1v = g.out_off ? g.out_off[bbA + 1] : bbA + 1;
+            oB0v = g.out_off ? g.out_off[bbZ] : bbZ; oB1v = g.out_off ? g.out_off[bbZ + 1] : bbZ + 1;
+        }
+    }
+    auto fanout_arrived = [&]() {
+        oA0 = __builtin_amdgcn_readfirstlane(oA0v); oA1 = __builtin_amdgcn_readfirstlane(oA1v);
+        oB0 = __builtin_amdgcn_readfirstlane(oB0v); oB1 = __builtin_amdgcn_readfirstlane(oB1v);
+        maxfan = R0 < Rend ? max(oA1 - oA0, oB1 - oB0) : 0;
+    };
+    auto request_ids = [&](int pp, int &kav, int &kbv) {       // adapters of pass pp for blocks A and B (-1: nothing to add)
+        kav = kbv = -1;
+        if (!has_lora || pp >= maxfan) return;
+        if (oA0 + pp < oA1) kav = g.adapter_of_out[oA0 + pp];
+        if (hasB && oB0 + pp < oB1) kbv = g.adapter_of_out[oB0 + pp];
+    };
+    const int it_ids = nk > 1 ? 1 : 0;
+
     // fragment rows are wm*MI*32 + i*32 + lm and wn*NJ*32 + j*32 + lm: (row >> 1) & 7 == (lm >> 1) & 7 for all
     const int fa0 = (wm * MI * 32 + lm) * BK, fb0 = A_EL + (wn * NJ * 32 + lm) * BK, sw = (lm >> 1) & 7;
     for (int it = 0; it < nk; ++it) {
@@ -365,6 +419,13 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
         else wait_vm_and_barrier<0>();
         // every wave is past compute(it - 1): its stage can be refilled
         if (it >= 1 && it + NS - 1 < nk) issue(it + NS - 1, (it - 1) % NS);
+        if constexpr (EK == 2) {
+            if (it == it_ids) {                               // (younger than every tile load in flight: the counted waits over-wait at most)
+                fanout_arrived();
+                request_ids(0, kAv, kBv);
+                request_ids(1, kAnv, kBnv);
+            }
+        }
         const bf16_t *cur = dsmem + (it % NS) * STAGE_EL;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
@@ -381,6 +442,162 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
         }
     }
     __syncthreads();   // all loads have landed (vmcnt(0) above) and all waves are done with the tiles
+
+    // ---- row-wise epilogue (bf16 output, two column subtiles per wave).  Per pass p the wave produces, for every row of its
+    // (MI * 32) x 64 region, the p-th output block of that row's input block: base product (+ bias, in the accumulators) + the
+    // low-rank terms of that output block, GELU, rounding to bf16 -- all in accumulator layout -- then the whole region goes through
+    // the wave's own LDS area once (8-byte writes, 16-byte reads, chunks swizzled by row & 7) and leaves as 128-byte row segments,
+    // eight rows per store instruction.  A 32-row subtile that straddles two input blocks adds each block's term with the
+    // other block's S rows zeroed, so block boundaries cost one more MFMA, not one more trip through LDS.
+    if constexpr (RW) {
+        bf16_t *stg16 = dsmem + wave * (RROWS * RCOLS);
+        if (R0 >= Rend) return;
+        if constexpr (EK == 1) {
+            fanout_arrived();
+            if (!two)
+                for (int bb = bbA + 1; bb < bbZ; ++bb) maxfan = max(maxfan, g.out_off ? g.out_off[bb + 1] - g.out_off[bb] : 1);
+        }
+        const bool gelu = g.mode == EPI_GELU;
+        const bf16_t *Sg = (const bf16_t *)g.S;
+        const int r8 = lane >> 3, ch = lane & 7;
+        const int col = n0 + wn * RCOLS + ch * 8;
+        const bool col_ok = col < g.N;
+
+        // one column subtile of results (accumulator layout, fp32) -> GELU -> bf16 -> the wave's staging rows [32 i, 32 i + 32)
+        auto stage1 = [&](const f32x16 &cj, int i, int j) {
+            const int srow = 32 * i + lm;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 v = {cj[4 * q], cj[4 * q + 1], cj[4 * q + 2], cj[4 * q + 3]};
+                if (gelu) v = gelu_poly4(v);
+                const bf16x4 w = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+                *(bf16x4 *)(stg16 + srow * RCOLS + ((((j * 4 + q) ^ (srow & 7)) << 3) + 4 * lh)) = w;
+            }
+        };
+        // rows of pass p: staging -> global, 8 rows x 128 bytes per instruction
+        auto store_rows = [&](int p) {
+            const int obA = (two && oA0 + p < oA1) ? oA0 + p : -1, obB = (two && hasB && oB0 + p < oB1) ? oB0 + p : -1;
+#pragma unroll 2
+            for (int q = 0; q < RROWS / 8; ++q) {
+                const int row = 8 * q + r8, t = R0 + row;
+                int ob, trow;
+                if (EK == 2 || two) {
+                    const bool inB = t >= tB;
+                    ob = inB ? obB : obA;
+                    trow = t - (inB ? tB : baseA);
+                } else {                                      // more than two input blocks in the region: looked up per row
+                    const int bb = min(t, Rend - 1) / Tblk;
+                    trow = t - bb * Tblk;
+                    const int o0 = g.out_off ? g.out_off[bb] : bb, o1 = g.out_off ? g.out_off[bb + 1] : bb + 1;
+                    ob = o0 + p < o1 ? o0 + p : -1;
+                }
+                if (t >= Rend || ob < 0 || !col_ok) continue;
+                const bf16x8 v = *(const bf16x8 *)(stg16 + row * RCOLS + ((ch ^ r8) << 3));
+                *(bf16x8 *)((bf16_t *)g.out + ((long)ob * g.Tout + g.t_off + trow) * g.N + col) = v;
+            }
+        };
+
+        if constexpr (EK == 2) {
+            // The host has checked: a region touches at most two input blocks, one low-rank term per output block, rank 8 or 16
+            // in one 16-rank step.  All operands of a pass -- the Bt fragments of the two adapters, one S fragment per subtile and
+            // one more for the subtile that straddles the block boundary -- are requested together, those of pass p + 1 before
+            // the rows of pass p are stored and the adapter ids of pass p + 2 with them: a pass never waits for more than what
+            // is left of one round trip.  (Bt columns past N and ranks past r are read from clamped addresses: the former
+            // feed columns that are never stored, the latter meet the zero padding of S.)
+            bf16x8 fwA[NJ], fwB[NJ], fs1[MI], fs2 = zero8;
+            auto request_operands = [&](int pp, int ka, int kb) {
+                const int j0 = min(lh * 8, g.r - 8);
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    const size_t bcol = (size_t)min(n0 + wn * RCOLS + j * 32 + lm, g.N - 1);
+                    if (ka >= 0) fwA[j] = *(const bf16x8 *)((const bf16_t *)g.Bt + ((size_t)ka * g.N + bcol) * g.r + j0);
+                    if (kb >= 0) fwB[j] = *(const bf16x8 *)((const bf16_t *)g.Bt + ((size_t)kb * g.N + bcol) * g.r + j0);
+                }
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+                    const int tw = R0 + 32 * i;
+                    const bool inB = tw >= tB;                    // the subtile's first block
+                    if ((inB ? kb : ka) >= 0 && tw < Rend) {
+                        const int trow = min(max(tw + lm - (inB ? tB : baseA), 0), Tblk - 1);
+                        fs1[i] = *(const bf16x8 *)(Sg + ((size_t)((inB ? oB0 : oA0) + pp) * Tblk + trow) * 16 + lh * 8);
+                    }
+                    if (!inB && tw + 32 > tB && tB < Rend && kb >= 0) {   // straddles the boundary: block B's rows of this subtile
+                        const int trow = min(max(tw + lm - tB, 0), Tblk - 1);
+                        fs2 = *(const bf16x8 *)(Sg + ((size_t)(oB0 + pp) * Tblk + trow) * 16 + lh * 8);
+                    }
+                }
+            };
+            kA = __builtin_amdgcn_readfirstlane(kAv); kB = __builtin_amdgcn_readfirstlane(kBv);
+            request_operands(0, kA, kB);
+            for (int p = 0; p < maxfan; ++p) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+                    const int tw = R0 + 32 * i;
+                    if (tw >= Rend) break;
+                    const bool inB = tw >= tB, both = !inB && tw + 32 > tB && tB < Rend && kB >= 0;
+                    const bf16x8 f1 = (inB || lm < tB - tw) ? fs1[i] : zero8;   // rows of the other block add nothing
+                    const bf16x8 f2 = lm >= tB - tw ? fs2 : zero8;
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {               // one column subtile at a time: 16 live result registers, not 32
+                        f32x16 cj = acc[i][j];
+                        if (inB) {
+                            if (kB >= 0) cj = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwB[j], f1, cj, 0, 0, 0);
+                        } else {
+                            if (kA >= 0) cj = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwA[j], f1, cj, 0, 0, 0);
+                            if (both) cj = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwB[j], f2, cj, 0, 0, 0);
+                        }
+                        stage1(cj, i, j);
+                    }
+                }
+                kA = __builtin_amdgcn_readfirstlane(kAnv); kB = __builtin_amdgcn_readfirstlane(kBnv);
+                if (p + 1 < maxfan) {
+                    request_operands(p + 1, kA, kB);
+                    request_ids(p + 2, kAnv, kBnv);
+                }
+                store_rows(p);
+            }
+        } else {
+            for (int p = 0; p < maxfan; ++p) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+                    const int tw = R0 + 32 * i;
+                    if (tw >= Rend) break;
+                    f32x16 c[NJ];
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) c[j] = acc[i][j];
+                    if (has_lora) {
+                        const int twe = min(tw + 32, Rend);
+                        const int b_lo = flat ? tw / Tblk : xb, b_hi = flat ? (twe - 1) / Tblk : xb;
+                        for (int bb = b_lo; bb <= b_hi; ++bb) {
+                            const int o0 = g.out_off ? g.out_off[bb] : bb, o1 = g.out_off ? g.out_off[bb + 1] : bb + 1;
+                            const int ob = o0 + p;
+                            if (ob >= o1) continue;
+                            const int rb0 = flat ? bb * Tblk : 0;
+                            const int lo = max(rb0 - tw, 0), hi = min(rb0 + Tblk - tw, 32);   // rows [lo, hi) of the subtile lie in block bb
+                            const int trow = min(max(tw + lm - rb0, 0), Tblk - 1);
+                            const int sb0 = g.set_off ? g.set_off[ob] : ob, sb1 = g.set_off ? g.set_off[ob + 1] : ob + 1;
+                            for (int sb = sb0; sb < sb1; ++sb) {
+                                const int k_ad = g.adapter_of_out[sb];
+                                if (k_ad < 0) continue;
+                                for (int s0 = 0; s0 < g.RP; s0 += 16) {
+                                    bf16x8 fsb = *(const bf16x8 *)(Sg + ((size_t)sb * Tblk + trow) * g.RP + s0 + lh * 8);
+                                    if (lm < lo || lm >= hi) fsb = zero8;
+                                    bf16x8 fwb[NJ];
+                                    load_fw(fwb, k_ad, s0);
+#pragma unroll
+                                    for (int j = 0; j < NJ; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwb[j], fsb, c[j], 0, 0, 0);
+                                }
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) stage1(c[j], i, j);
+                }
+                store_rows(p);
+            }
+        }
+        return;
+    }
 
     // ---- epilogue, wave by wave and 32 rows at a time: no workgroup barrier is needed because each wave stages
     // through its own LDS region and the LDS executes one wave's instructions in order.
@@ -622,6 +839,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g)
 
 }  // namespace
 
+template <int BM, int BN, int WM, int WN, int NS> static void launch_dma(const GemmArgs &g, hipStream_t st);
+
 // grid of the XCD order: every XCD gets ceil(tiles / 8) workgroups
 static unsigned dma_grid(int tiles_mtot, int tiles_n)
 {
@@ -629,11 +848,11 @@ static unsigned dma_grid(int tiles_mtot, int tiles_n)
     return (unsigned)((total + 7) / 8 * 8);
 }
 
-template <int BM, int BN, int WM, int WN, int NS>
-static void launch_dma(const GemmArgs &g, hipStream_t st)
+template <int BM, int BN, int WM, int WN, int NS, int EK>
+static void launch_dma_ek(const GemmArgs &g, hipStream_t st)
 {
     constexpr int LDS = NS * (BM + BN) * 64 * 2;
-    auto kern = gemm_bf16_dma_kernel<BM, BN, WM, WN, NS>;
+    auto kern = gemm_bf16_dma_kernel<BM, BN, WM, WN, NS, EK>;
     if (LDS > 64 * 1024) {
         static bool attr_set = false;   // raising the dynamic LDS limit is a per-kernel, process-wide setting
         if (!attr_set) {
@@ -643,6 +862,22 @@ static void launch_dma(const GemmArgs &g, hipStream_t st)
     }
     const int tiles_m = (g.T + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     POLY_LAUNCH_SHMEM(POLY_STAGE_GEMM, kern, dim3(dma_grid(g.n_in * tiles_m, tiles_n)), dim3(64 * WM * WN), LDS, st, g, tiles_m, tiles_n);
+}
+
+template <int BM, int BN, int WM, int WN, int NS>
+static void launch_dma(const GemmArgs &g, hipStream_t st)
+{
+    if constexpr (BN / WN == 64) {
+        if (g.mode != EPI_RESID) {
+            // a wave's region of BM / WM rows touches at most two input blocks when a block is at least that long (or when tiles
+            // stay inside blocks: Tb == 0)
+            const bool two_blocks = g.Tb == 0 || g.Tb >= BM / WM;
+            if (two_blocks && !g.set_off && (!g.S || (g.RP == 16 && g.r % 8 == 0))) launch_dma_ek<BM, BN, WM, WN, NS, 2>(g, st);
+            else launch_dma_ek<BM, BN, WM, WN, NS, 1>(g, st);
+            return;
+        }
+    }
+    launch_dma_ek<BM, BN, WM, WN, NS, 0>(g, st);
 }
 
 static int launch_gemm_dma(const GemmArgs &g, hipStream_t st)

@@ -223,7 +223,8 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
             g.out_off = fan ? row_offsets : nullptr;
             if (use(0)) {
                 const void *At = lora_ptr(lora->At[0], 0, D, 3 * D, true), *Bt = lora_ptr(lora->Bt[0], 0, D, 3 * D, false);
-                POLY_TRY(launch_shrink(w.u, T, D, At, m->r, RP, m->lora_scale, R, R_dev, summed ? shrink_map : fan_map, w.adapter_of_row, w.S, dt, st));
+                POLY_TRY(launch_shrink(w.u, T, D, At, m->r, RP, m->lora_scale, R, R_dev, summed ? shrink_map : fan_map, w.adapter_of_row,
+                                       (summed || fan) ? row_offsets : nullptr, w.S, dt, st));
                 lora_gemm(g, 0, Bt);
             }
             g.mode = EPI_STORE; g.out = w.qkv; g.Tout = T;
@@ -267,7 +268,8 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
             g.T = T; g.K = D; g.N = D; g.n_in = n_out; g.n_in_dev = n_out_dev;
             if (use(1)) {
                 const void *At = lora_ptr(lora->At[1], 1, D, D, true), *Bt = lora_ptr(lora->Bt[1], 1, D, D, false);
-                POLY_TRY(launch_shrink(w.o, T, D, At, m->r, RP, m->lora_scale, R, R_dev, shrink_map, w.adapter_of_row, w.S, dt, st));
+                POLY_TRY(launch_shrink(w.o, T, D, At, m->r, RP, m->lora_scale, R, R_dev, shrink_map, w.adapter_of_row, summed ? row_offsets : nullptr,
+                                       w.S, dt, st));
                 lora_gemm(g, 1, Bt);
             }
             g.mode = EPI_RESID; g.out = x_out; g.Tout = T; g.res = x_in; g.res_block_of_out = fan_map;
@@ -294,7 +296,8 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
             g.T = T; g.K = D; g.N = Dm; g.n_in = n_out; g.n_in_dev = n_out_dev;
             if (use(2)) {
                 const void *At = lora_ptr(lora->At[2], 2, D, Dm, true), *Bt = lora_ptr(lora->Bt[2], 2, D, Dm, false);
-                POLY_TRY(launch_shrink(w.u, T, D, At, m->r, RP, m->lora_scale, R, R_dev, shrink_map, w.adapter_of_row, w.S, dt, st));
+                POLY_TRY(launch_shrink(w.u, T, D, At, m->r, RP, m->lora_scale, R, R_dev, shrink_map, w.adapter_of_row, summed ? row_offsets : nullptr,
+                                       w.S, dt, st));
                 lora_gemm(g, 2, Bt);
             }
             g.mode = EPI_GELU; g.out = w.h; g.Tout = T;
@@ -306,7 +309,8 @@ int forward_impl(const poly_model_desc *m, const poly_base_weights *base, const 
             g.T = T; g.K = Dm; g.N = D; g.n_in = n_out; g.n_in_dev = n_out_dev;
             if (use(3)) {
                 const void *At = lora_ptr(lora->At[3], 3, Dm, D, true), *Bt = lora_ptr(lora->Bt[3], 3, Dm, D, false);
-                POLY_TRY(launch_shrink(w.h, T, Dm, At, m->r, RP, m->lora_scale, R, R_dev, shrink_map, w.adapter_of_row, w.S, dt, st));
+                POLY_TRY(launch_shrink(w.h, T, Dm, At, m->r, RP, m->lora_scale, R, R_dev, shrink_map, w.adapter_of_row, summed ? row_offsets : nullptr,
+                                       w.S, dt, st));
                 lora_gemm(g, 3, Bt);
             }
             g.mode = EPI_RESID; g.out = x_out; g.Tout = T; g.res = x_out;
@@ -402,7 +406,7 @@ int lora_linear_impl(const void *X, int n_xblocks, int T, int Kdim, const void *
 
     POLY_TRY(launch_prep(row_offsets, adapter_ids, n_xblocks, R, n_adapters, w.meta, w.frame_of_row, w.adapter_of_row, dev_status, st));
     if (R == 0) return POLY_OK;
-    POLY_TRY(launch_shrink(X, T, Kdim, At, r, RP, scale, R, &w.meta->R, w.frame_of_row, w.adapter_of_row, w.S, dtype, st));
+    POLY_TRY(launch_shrink(X, T, Kdim, At, r, RP, scale, R, &w.meta->R, w.frame_of_row, w.adapter_of_row, row_offsets, w.S, dtype, st));
     GemmArgs g = {};
     g.A = X; g.Wt = Wt; g.bias = bias; g.T = T; g.K = Kdim; g.N = Ndim;
     g.n_in = n_xblocks; g.n_in_dev = &w.meta->F_ok; g.out_off = row_offsets;

@@ -250,10 +250,12 @@ int launch_rowlin(const RowLinArgs &a, hipStream_t st);
 int launch_layernorm(const float *x, void *y, const float *gain, const float *shift, int D, float eps, int T,
                      int n_blocks, const int *n_blocks_dev, int dtype, hipStream_t st);
 
-// S[ob] = scale * X[in_block_of_out[ob]] At[adapter_of_out[ob]]^T, zero padded to RP columns
+// S[ob] = scale * X[in_block_of_out[ob]] At[adapter_of_out[ob]]^T, zero padded to RP columns.  pair_off (nullable): CSR offsets
+// [n_in + 1] of the output blocks of every input block, when the output blocks of one input block are consecutive (fan-out):
+// lets one workgroup serve two of them from one read of the input rows
 int launch_shrink(const void *X, int T, int K, const void *At, int r, int RP, float scale, int n_out,
-                  const int *n_out_dev, const int *in_block_of_out, const int *adapter_of_out, void *S, int dtype,
-                  hipStream_t st);
+                  const int *n_out_dev, const int *in_block_of_out, const int *adapter_of_out, const int *pair_off, void *S,
+                  int dtype, hipStream_t st);
 
 // softmax attention of every (block, head); qkv elt [n*T][3D] -> out elt [n*T][D]
 int launch_attention(const void *qkv, void *out, int T, int D, int heads, int n_blocks, const int *n_blocks_dev,

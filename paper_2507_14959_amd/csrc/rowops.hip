@@ -148,27 +148,42 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *x, T *y
 // from global memory (each lane 16 contiguous bytes along K). The four waves take a quarter of K each, so a
 // short row still has many loads in flight; the partial sums meet in LDS and every wave finishes eight of the
 // rows. Result zero padded to RP columns.
+// With ranks of at most 16 a 32 x 32 MFMA tile has room for two adapters: where consecutive output blocks read the
+// same input block (the fan-out of a frame into its row-blocks; pair_off = the CSR offsets of the input blocks) the
+// workgroup of the even one does both -- columns 0-15 adapter k(ob), 16-31 adapter k(ob + 1) -- and the input rows
+// are read once instead of twice.
 __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *X, int T, int K, const bf16_t *At, int r, int RP,
                                                           float scale, int n_out, const int *n_out_dev,
-                                                          const int *in_block_of_out, const int *adapter_of_out, bf16_t *S)
+                                                          const int *in_block_of_out, const int *adapter_of_out, const int *pair_off,
+                                                          bf16_t *S)
 {
     __shared__ float red[4][16][64];
     const int subs = (T + 31) / 32;
     const int ob = blockIdx.x / subs, sub = blockIdx.x % subs;
     const int n = n_out_dev ? min(*n_out_dev, n_out) : n_out;
     if (ob >= n) return;
-    const int k_ad = adapter_of_out[ob];
-    if (k_ad < 0) return;
     const int xb = in_block_of_out ? in_block_of_out[ob] : ob;
+    const bool paired = pair_off && in_block_of_out && RP == 16;
+    int ob2 = -1;
+    if (paired) {
+        if ((ob - pair_off[xb]) & 1) return;                 // done by the workgroup of ob - 1
+        if (ob + 1 < min(pair_off[xb + 1], n)) ob2 = ob + 1;
+    }
+    const int k_ad = adapter_of_out[ob], k_ad2 = ob2 >= 0 ? adapter_of_out[ob2] : -1;
+    if (k_ad < 0 && k_ad2 < 0) return;
     const int q = threadIdx.x >> 6, lane = threadIdx.x & 63, lm = lane & 31, lh = lane >> 5;
     const int t = sub * 32 + lm;
     const bf16_t *xr = X + ((size_t)xb * T + min(t, T - 1)) * K + lh * 8;
     const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     const int steps = (K + 15) / 16, per = (steps + 3) / 4;
     const int s0 = q * per, s1 = min(steps, s0 + per);
-    for (int j0 = 0; j0 < RP; j0 += 32) {
+    for (int j0 = 0; j0 < (paired ? 32 : RP); j0 += 32) {
+        // column j0 + lm of the MFMA tile: rank `rank` of adapter `ksel`, stored to output block `osel`
         const int j = j0 + lm;
-        const bf16_t *ar = At + ((size_t)k_ad * r + min(j, r - 1)) * K + lh * 8;
+        const bool second = paired && lm >= 16;
+        const int rank = paired ? (lm & 15) : j, ksel = second ? k_ad2 : k_ad, osel = second ? ob2 : ob;
+        const bool col_live = ksel >= 0 && rank < r;
+        const bf16_t *ar = At + ((size_t)max(ksel, 0) * r + min(rank, r - 1)) * K + lh * 8;
         f32x16 acc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[e] = 0.f;
@@ -180,7 +195,7 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *X, int T
                 const int k = (st + u) * 16;
                 const bool kin = k + lh * 8 + 8 <= K;
                 fa[u] = (t < T && kin) ? *(const bf16x8 *)(xr + k) : zero8;
-                fb[u] = (j < r && kin) ? *(const bf16x8 *)(ar + k) : zero8;
+                fb[u] = (col_live && kin) ? *(const bf16x8 *)(ar + k) : zero8;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u], fb[u], acc, 0, 0, 0);
@@ -189,20 +204,20 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *X, int T
             const int k = st * 16;
             const bool kin = k + lh * 8 + 8 <= K;
             const bf16x8 fa = (t < T && kin) ? *(const bf16x8 *)(xr + k) : zero8;
-            const bf16x8 fb = (j < r && kin) ? *(const bf16x8 *)(ar + k) : zero8;
+            const bf16x8 fb = (col_live && kin) ? *(const bf16x8 *)(ar + k) : zero8;
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
         }
         if (j0) __syncthreads();
 #pragma unroll
         for (int e = 0; e < 16; ++e) red[q][e][lane] = acc[e];
         __syncthreads();
-        if (j < RP) {
+        if (paired ? (ksel >= 0) : (j < RP && k_ad >= 0)) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int e = 4 * q + i;
                 const float v = red[0][e][lane] + red[1][e][lane] + red[2][e][lane] + red[3][e][lane];
                 const int tt = sub * 32 + 8 * q + 4 * lh + i;
-                if (tt < T) S[((size_t)ob * T + tt) * RP + j] = (bf16_t)(scale * v);
+                if (tt < T) S[((size_t)osel * T + tt) * RP + (paired ? rank : j)] = (bf16_t)(scale * v);
             }
         }
     }
@@ -369,7 +384,7 @@ int launch_layernorm(const float *x, void *y, const float *gain, const float *sh
 }
 
 int launch_shrink(const void *X, int T, int K, const void *At, int r, int RP, float scale, int n_out, const int *n_out_dev,
-                  const int *in_block_of_out, const int *adapter_of_out, void *S, int dtype, hipStream_t st)
+                  const int *in_block_of_out, const int *adapter_of_out, const int *pair_off, void *S, int dtype, hipStream_t st)
 {
     if (n_out == 0) return POLY_OK;
     if (dtype == POLY_BF16) {
@@ -377,7 +392,7 @@ int launch_shrink(const void *X, int T, int K, const void *At, int r, int RP, fl
         const int subs = (T + 31) / 32;
         const unsigned blocks = (unsigned)((size_t)n_out * subs);
         POLY_LAUNCH(POLY_STAGE_SHRINK, shrink_bf16_kernel, dim3(blocks), dim3(256), st, (const bf16_t *)X, T, K, (const bf16_t *)At, r, RP, scale, n_out,
-                           n_out_dev, in_block_of_out, adapter_of_out, (bf16_t *)S);
+                           n_out_dev, in_block_of_out, adapter_of_out, pair_off, (bf16_t *)S);
     } else {
         const size_t total = (size_t)n_out * T * RP;
         const unsigned blocks = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);

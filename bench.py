@@ -22,9 +22,19 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch of the linear kernels on the default workload: FETCH_SIZE + WRITE_SIZE from two rocprofv3 --pmc
-# runs of this script, scaled by a copy kernel of known size (profiles/bench_cfg2_deit_tiny_hbm_traffic.md)
-LINEAR_HBM_BYTES_PER_LAUNCH = 33.7e6
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "bench_cfg2_deit_tiny_hbm_traffic.md")
+
+
+def measured_traffic_per_launch():
+    """HBM bytes per launch of the linear kernels on the default workload, as the tracked rocprofv3 counter summary states it
+    (FETCH_SIZE + WRITE_SIZE from two --pmc runs of this script, scaled by a copy of known size); None if the file has no figure."""
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            if line.startswith("linear_hbm_bytes_per_launch:"):
+                return float(line.split(":")[1].split()[0])
+    except OSError:
+        pass
+    return None
 
 
 def scores_for_sets(off, ids, n_groups=16, group_size=5):
@@ -87,10 +97,11 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--L0", type=int, default=0, help="first adapted layer (0 = all layers adapted; 10 = last 20 %%)")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-checker baseline")
-    ap.add_argument("--no-extra", action="store_true", help="skip the side measurements (L0=10, isolated linear)")
-    ap.add_argument("--sweep", action="store_true",
-                    help="also print a second JSON line: frames/s for 1..5 adapters per frame, all layers adapted vs the last 20 %% only")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-checker baseline and the error figures against it")
+    ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
+    ap.add_argument("--only", default=None,
+                    choices=["cfg5", "cfg3", "cfg4", "loop", "sweep", "tau", "sum", "preset"],
+                    help="run ONE side workload alone and print its JSON (so that a profiler's kernel rows belong to one workload)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 256 MiB device copy (a kernel of known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -101,6 +112,9 @@ def main():
 
     import torch
     from paper_2507_14959_amd import binding, synth
+    oracle = None
+    if not args.no_cpu:
+        import oracle
 
     dev = "cuda"
     cfg, w, frames_np, off_np, ids_np = synth.make_forward_case(2)
@@ -139,6 +153,251 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
+    up = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).to(device=dev, dtype=dt).contiguous()
+
+    # ------------------------------------------------------------------ side workloads (each also runs alone: --only NAME)
+
+    def run_cfg5():
+        """Isolated multi-LoRA linear (config 5): 256 x 197 x 768 -> 2304, 64 adapters r=16, 2 per block."""
+        case = synth.make_lora_linear_case()
+        elt = torch.bfloat16
+        X, Wt = up(case["X"], elt), up(case["W"].T, elt)
+        At, Bt = up(np.swapaxes(case["A"], 1, 2), elt), up(np.swapaxes(case["B"], 1, 2), elt)
+        bias = up(case["bias"], torch.float32)
+        o5, i5 = up(case["row_offsets"], torch.int32), up(case["adapter_ids"], torch.int32)
+        R5 = int(case["row_offsets"][-1])
+        Y = torch.empty(R5, 197, 2304, dtype=elt, device=dev)
+        ws5 = torch.empty(binding.poly_lora_linear_workspace_bytes(256, 197, 16, R5, 1), dtype=torch.uint8, device=dev)
+        run5 = lambda: binding.poly_lora_linear(X, Wt, bias, At, Bt, 1.0, o5, i5, R5, Y, ws5)
+        for _ in range(5):
+            run5()
+        torch.cuda.synchronize()
+        binding.poly_profile_begin(256)
+        for _ in range(20):
+            run5()
+        p5 = binding.poly_profile_end()
+        fl5 = 2.0 * 256 * 197 * 768 * 2304 + 2.0 * R5 * 197 * 16 * 2304        # base once per X block + expand
+        sh5 = 2.0 * R5 * 197 * 768 * 16
+        by5 = 2.0 * (256 * 197 * 768 + R5 * 197 * 2304 + 768 * 2304 + R5 * 197 * 16 + 64 * 16 * 2304)   # X, Y, W, S, Bt
+        g5 = p5["gemm"]["ms"] / p5["gemm"]["launches"] * 1e-3
+        s5 = p5["shrink"]["ms"] / p5["shrink"]["launches"] * 1e-3
+        sby = 2.0 * (256 * 197 * 768 + R5 * 197 * 16 + 64 * 16 * 768)           # every X block once, S, the adapters' A
+        res = {"gemm_us": round(g5 * 1e6, 1), "gemm_tflops": round(fl5 / g5 / 1e12, 1),
+               "gemm_frac_mfma": round(fl5 / g5 / 1e12 / PEAK_BF16_TFLOPS, 4),
+               "gemm_GBs": round(by5 / g5 / 1e9, 1), "gemm_frac_hbm": round(by5 / g5 / 1e9 / PEAK_HBM_GBS, 4),
+               "shrink_us": round(s5 * 1e6, 1), "shrink_GBs": round(sby / s5 / 1e9, 1),
+               "shrink_frac_hbm": round(sby / s5 / 1e9 / PEAK_HBM_GBS, 4), "shrink_gflops": round(sh5 / s5 / 1e9, 1),
+               "whole_call_tflops": round((fl5 + sh5) / (g5 + s5) / 1e12, 1),
+               "whole_call_frac_mfma": round((fl5 + sh5) / (g5 + s5) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+        if oracle is not None:
+            torch.cuda.synchronize()
+            sample = (0, 129, 255, 300, 511)
+            Yh = Y[list(sample)].float().cpu().numpy()
+            err = max(float(np.abs(Yh[n] - oracle.lora_linear(case, b_begin=b, b_end=b + 1)[0]).max()) for n, b in enumerate(sample))
+            res["max_abs_error_vs_oracle"] = {"value": err, "sample": "5 of 512 row-blocks (all of them in tests/test_gpu_lora_linear.py)"}
+        return res
+
+    def run_cfg3():
+        """Config 3: ViT-base, 64 frames, adapters on qkv, proj, fc1 and fc2 (forward alone; its adapter sets are given)."""
+        cfg3, w3, frames3_np, off3_np, ids3_np = synth.make_forward_case(3)
+        model3 = binding.DeviceModel(cfg3, w3, L0=0)
+        frames3 = model3.frames_to_device(frames3_np)
+        F3, R3 = frames3_np.shape[0], int(off3_np[-1])
+        off3, ids3 = up(off3_np, torch.int32), up(ids3_np, torch.int32)
+        out3 = torch.zeros(R3, cfg3.C, device=dev)
+        lg3 = torch.zeros(R3, cfg3.C, device=dev)
+        ws3 = torch.empty(binding.poly_forward_workspace_bytes(model3, F3, R3), dtype=torch.uint8, device=dev)
+        call = lambda: binding.poly_forward(model3, frames3, off3, ids3, R3, out3, ws3, out_logits=lg3)
+        sec3 = timed(call, 10, 3)
+        binding.poly_profile_begin(4096)
+        for _ in range(5):
+            call()
+        p3 = binding.poly_profile_end()
+        T3 = cfg3.T
+        rows3 = R3 * T3
+        fl3 = R3 * cfg3.L * (2.0 * T3 * (4 * cfg3.D ** 2 + 2 * cfg3.D * cfg3.Dm) + 4.0 * T3 * T3 * cfg3.D
+                             + 2.0 * T3 * cfg3.r * (4 * cfg3.D + 2 * cfg3.D + 2 * (cfg3.D + cfg3.Dm))) + F3 * 2.0 * (T3 - 1) * 768 * cfg3.D
+        ln_us = p3["layernorm"]["ms"] / p3["layernorm"]["launches"] * 1e3
+        ln_bytes = rows3 * cfg3.D * (4 + 2)                                      # fp32 row in, bf16 row out
+        sh_us = p3["shrink"]["ms"] / p3["shrink"]["launches"] * 1e3
+        # per layer: shrink inputs of width D, D, D and Dm (bf16) + S out + the distinct adapters' A
+        sh_bytes = (rows3 * 2.0 * (3 * cfg3.D + cfg3.Dm) + 4 * rows3 * 16 * 2.0) / 4
+        res = {"frames_per_s": round(F3 / sec3, 1), "ms_per_call": round(sec3 * 1e3, 2), "row_blocks": R3,
+               "algorithmic_tflops": round(fl3 / sec3 / 1e12, 1), "frac_mfma": round(fl3 / sec3 / 1e12 / PEAK_BF16_TFLOPS, 4),
+               "stage_ms_per_call": {k: round(v["ms"] / 5, 3) for k, v in p3.items() if v["launches"]},
+               "layernorm_us_per_launch": round(ln_us, 1), "layernorm_GBs": round(ln_bytes / ln_us / 1e3, 1),
+               "layernorm_frac_hbm": round(ln_bytes / ln_us / 1e3 / PEAK_HBM_GBS, 4),
+               "shrink_us_per_launch": round(sh_us, 1), "shrink_GBs": round(sh_bytes / sh_us / 1e3, 1),
+               "shrink_frac_hbm": round(sh_bytes / sh_us / 1e3 / PEAK_HBM_GBS, 4)}
+        if oracle is not None:
+            torch.cuda.synchronize()
+            fs = (0, 37)
+            o1, i1 = synth.sets_to_csr([list(ids3_np[off3_np[f]:off3_np[f + 1]]) for f in fs])
+            want = oracle.forward(cfg3, w3, frames3_np[list(fs)], o1, i1)["logits"]
+            got = np.concatenate([lg3.cpu().numpy()[off3_np[f]:off3_np[f + 1]] for f in fs])
+            res["max_abs_logit_error_vs_oracle"] = {"value": float(np.abs(got - want).max()),
+                                                    "sample": f"frames {fs} ({len(i1)} of {R3} row-blocks; all of them in tests/test_gpu_forward.py)"}
+        return res
+
+    def stream_frames():
+        return binding.DeviceModel(cfg, w, L0=0).frames_to_device(synth.make_frames(cfg, 64, np.random.default_rng(synth.seed_of(4))))
+
+    def run_cfg4():
+        """Config 4: a 1024-frame label stream in 16 batches of 64 frames, poly_select + poly_forward per batch on the DeiT-tiny model
+        (every batch reuses the same 64 synthetic frames: the cost of a batch depends on its adapter sets, not its pixels)."""
+        scores4_np, _ = synth.make_label_stream(1024)
+        model4 = binding.DeviceModel(cfg, w, L0=0)
+        frames4 = stream_frames()
+        scores4, mem4 = up(scores4_np, torch.float32), up(mem_np, torch.uint8)
+        cap4 = 3 * 64
+        off4 = torch.zeros(65, dtype=torch.int32, device=dev)
+        ids4 = torch.zeros(cap4, dtype=torch.int32, device=dev)
+        cnt4 = torch.zeros(2, dtype=torch.int32, device=dev)
+        out4 = torch.zeros(cap4, cfg.C, device=dev)
+        merged4 = torch.zeros(64, K_labels, device=dev)
+        ws4 = torch.empty(binding.poly_forward_workspace_bytes(model4, 64, cap4), dtype=torch.uint8, device=dev)
+
+        def stream_pass():
+            for a0 in range(0, 1024, 64):
+                binding.poly_select(scores4[a0:a0 + 64], mem4, off4, ids4, cnt4)
+                binding.poly_forward(model4, frames4, off4, ids4, cap4, out4, ws4, out_merged=merged4)
+        sec4 = timed(stream_pass, 5, 2)
+        # the whole stream's context sets in one call, for the stream statistics of Sec. 3.4
+        offs = torch.zeros(1025, dtype=torch.int32, device=dev)
+        idss = torch.zeros(1024 * 3, dtype=torch.int32, device=dev)
+        binding.poly_select(scores4, mem4, offs, idss, cnt4)
+        torch.cuda.synchronize()
+        n = int(cnt4.cpu().numpy()[0])
+        cov, sw = binding.poly_stream_metrics(offs.cpu().numpy(), idss.cpu().numpy()[:n], mem_np.shape[0])
+        res = {"frames_per_s": round(1024 / sec4, 1), "ms_per_64_frame_batch": round(sec4 / 16 * 1e3, 3),
+               "avg_coverage": round(cov, 4), "switch_penalty": sw, "uncovered_labels": int(cnt4.cpu().numpy()[1])}
+        if oracle is not None:
+            o_off, o_ids, _ = oracle.select(scores4_np, mem_np)
+            res["adapter_sets_equal_oracle"] = bool(np.array_equal(offs.cpu().numpy(), o_off) and np.array_equal(idss.cpu().numpy()[:n], o_ids))
+        return res
+
+    def run_loop():
+        """The lagged loop (Fig. 3b): the paper's placement (adapters on the last 20 % of the layers), a base head over the 80 labels
+        on the shared layers' output, Alg. 2 on the previous frame's scores, then the adapted layers; one call per 64 frames of the
+        stream, nothing comes back to the host between the steps."""
+        model6 = binding.DeviceModel(cfg, w, L0=10)
+        frames4 = stream_frames()
+        bw6, bb6 = synth.make_base_head(cfg, K_labels, 78, bias_mean=-5.0)
+        s6 = binding.DeviceStream(model6, bw6, bb6, mem_np)
+        cap6 = 4 * 64
+        off6 = torch.zeros(65, dtype=torch.int32, device=dev)
+        ids6 = torch.zeros(cap6, dtype=torch.int32, device=dev)
+        cnt6 = torch.zeros(2, dtype=torch.int32, device=dev)
+        out6 = torch.zeros(cap6, cfg.C, device=dev)
+        base6 = torch.zeros(64, K_labels, device=dev)
+        merged6 = torch.zeros(64, K_labels, device=dev)
+        ws6 = torch.empty(binding.poly_stream_step_workspace_bytes(model6, 64, cap6, K_labels), dtype=torch.uint8, device=dev)
+
+        def loop_pass():
+            for _ in range(16):
+                binding.poly_stream_step(model6, s6, frames4, cap6, off6, ids6, cnt6, out6, ws6, out_base_scores=base6, out_merged=merged6)
+        sec6 = timed(loop_pass, 5, 2)
+        return {"frames_per_s": round(1024 / sec6, 1), "ms_per_64_frame_call": round(sec6 / 16 * 1e3, 3),
+                "row_blocks_last_call": int(cnt6.cpu().numpy()[0])}
+
+    def run_sweep():
+        """Adapters per frame x placement (the synthetic analogue of the paper's Figs. 3-4): every frame gets exactly n adapters, ids
+        uniform without replacement; the step is the same select + forward + merge as the headline."""
+        rng = np.random.default_rng(synth.seed_of(2) + 77)
+        table = {}
+        for n_ad in range(1, 6):
+            ids_s = np.concatenate([np.sort(rng.choice(cfg.n_adapters, size=n_ad, replace=False)) for _ in range(F)]).astype(np.int32)
+            off_s = (np.arange(F + 1) * n_ad).astype(np.int32)
+            sc_s = scores_for_sets(off_s, ids_s)
+            row = {}
+            for L0s in (0, cfg.polymorph_L0()):
+                step_s, keep_s = make_step(L0s, sc_s, 5)
+                sec_s = timed(step_s, 40, 8)
+                assert np.array_equal(keep_s[4].cpu().numpy(), off_s) and np.array_equal(keep_s[5].cpu().numpy()[:len(ids_s)], ids_s)
+                row[f"L0={L0s}"] = round(F / sec_s, 1)
+                del step_s, keep_s
+            table[str(n_ad)] = row
+        return {"unit": "frames/s, config-2 model, 32 frames, n adapters on every frame", "adapters_per_frame": table}
+
+    def run_tau():
+        """Overlapping contexts (Alg. 1 with overlap on the synthetic co-occurrence matrix: 45 contexts of up to 5 over 80 labels), a
+        synthetic accuracy table a_{C,l} and the 1024-frame label stream in one stateful poly_select call per tau: contexts per frame
+        (AvgCoverage), changes of the set (SwitchPenalty) and labels nobody provides, without / with context copy (Sec. 3.5, Table 4)."""
+        cooc, _, n_img = synth.make_cooccurrence(p_partner=0.5, seed=2003, shuffle=False)
+        mem45, unplaced = binding.poly_build_contexts(cooc, 5, 45, allow_overlap=True)
+        M = mem45.shape[0]
+        acc = synth.make_accuracy_table(mem45)
+        scores4_np, _ = synth.make_label_stream(1024)
+        sc, memd, accd = up(scores4_np, torch.float32), up(mem45, torch.uint8), up(acc, torch.float32)
+        off = torch.zeros(1025, dtype=torch.int32, device=dev)
+        ids = torch.zeros(1024 * 8, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(2, dtype=torch.int32, device=dev)
+        rows, exact = {}, True
+        us = []
+        for tau in (0.1, 0.3, 0.5, 0.7, 0.9):
+            row = {}
+            for copy in (False, True):
+                state = torch.zeros(binding.poly_select_state_bytes(80), dtype=torch.uint8, device=dev)
+                binding.poly_select(sc, memd, off, ids, cnt, acc=accd, tau=tau, context_copy=copy, state=state)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                state.zero_()
+                binding.poly_select(sc, memd, off, ids, cnt, acc=accd, tau=tau, context_copy=copy, state=state)
+                torch.cuda.synchronize()
+                us.append((time.perf_counter() - t0) * 1e6)
+                c = cnt.cpu().numpy()
+                o_h, i_h = off.cpu().numpy(), ids.cpu().numpy()[:int(c[0])]
+                cov, sw = binding.poly_stream_metrics(o_h, i_h, M)
+                row["copy" if copy else "plain"] = {"avg_coverage": round(cov, 4), "switch_penalty": sw, "uncovered": int(c[1])}
+                if oracle is not None:
+                    o_off, o_ids, o_unc = oracle.select(scores4_np, mem45, acc=acc, tau=tau, context_copy=copy, state=oracle.SelectState(80, M))
+                    exact = exact and np.array_equal(o_h, o_off) and np.array_equal(i_h, o_ids) and o_unc == int(c[1])
+            rows[str(tau)] = row
+        res = {"contexts": M, "labels_in_no_context": unplaced,
+               "intra_coherence": round(binding.poly_intra_coherence(cooc, mem45, norm=n_img), 5),
+               "select_us_per_1024_frame_call": round(float(np.median(us)), 1), "by_tau": rows}
+        if oracle is not None:
+            res["adapter_sets_equal_oracle"] = bool(exact)
+        return res
+
+    def forward_rate(cfg_x, w_x, frames_x, off_x, ids_x, L0, compose, n_check):
+        model = binding.DeviceModel(cfg_x, w_x, L0=L0, compose=compose)
+        fr = model.frames_to_device(frames_x)
+        Fx, Rx = frames_x.shape[0], int(off_x[-1])
+        off, ids = up(off_x, torch.int32), up(ids_x, torch.int32)
+        out = torch.zeros(Rx, cfg_x.C, device=dev)
+        lg = torch.zeros(Rx, cfg_x.C, device=dev)
+        ws = torch.empty(binding.poly_forward_workspace_bytes(model, Fx, Rx), dtype=torch.uint8, device=dev)
+        sec = timed(lambda: binding.poly_forward(model, fr, off, ids, Rx, out, ws, out_logits=lg), 30, 5)
+        res = {"frames_per_s": round(Fx / sec, 1), "ms_per_call": round(sec * 1e3, 3), "row_blocks": Rx}
+        if oracle is not None:
+            torch.cuda.synchronize()
+            o1, i1 = synth.sets_to_csr([list(ids_x[off_x[f]:off_x[f + 1]]) for f in range(n_check)])
+            want = oracle.forward(cfg_x, w_x, frames_x[:n_check], o1, i1, L0=L0, compose=compose)["logits"]
+            res["max_abs_logit_error_vs_oracle"] = {"value": float(np.abs(lg.cpu().numpy()[:len(i1)] - want).max()),
+                                                    "sample": f"the first {n_check} frames ({len(i1)} row-blocks)"}
+        return res
+
+    def run_sum():
+        """The other reading of Sec. 3.1: all of a frame's adapters summed on ONE hidden state (config-2 model and adapter sets)."""
+        return {"L0=0": forward_rate(cfg, w, frames_np, off_np, ids_np, 0, "sum", 4),
+                "L0=10": forward_rate(cfg, w, frames_np, off_np, ids_np, 10, "sum", 4)}
+
+    def run_preset():
+        """The setting the paper trains (Sec. 4): rank 16 with scaling 32 (s = 2) on query and value only, adapters on the last two
+        layers, 11 contexts with 5-class heads; branch per adapter and summed."""
+        cfg_p, w_p, fr_p, off_p, ids_p = synth.make_paper_preset(F=32)
+        return {"branch": forward_rate(cfg_p, w_p, fr_p, off_p, ids_p, cfg_p.L0, "branch", 4),
+                "sum": forward_rate(cfg_p, w_p, fr_p, off_p, ids_p, cfg_p.L0, "sum", 4)}
+
+    side = {"cfg5": ("lora_linear_cfg5", run_cfg5), "cfg4": ("stream_cfg4", run_cfg4), "loop": ("lagged_loop_L0_10", run_loop),
+            "cfg3": ("vit_base_cfg3", run_cfg3), "sweep": ("adapter_sweep", run_sweep), "tau": ("tau_sweep_overlapping_contexts", run_tau),
+            "sum": ("sum_composition_cfg2", run_sum), "preset": ("paper_preset_qv_r16_s2_L0_10", run_preset)}
+    if args.only:
+        name, fn = side[args.only]
+        print(json.dumps({"only": name, "result": fn()}))
+        return
+
     if args.calib_copy:
         src = torch.zeros(64 << 20, dtype=torch.float32, device=dev)      # 256 MiB
         dst = torch.empty_like(src)
@@ -164,10 +423,17 @@ def main():
     assert g["launches"] == n_gemm * n_prof, (g, n_gemm)
     avg_ms = g["ms"] / g["launches"]
     achieved = flops / n_gemm / (avg_ms * 1e-3) / 1e12
+    # what the method has to move per step (frames, base weights once, the distinct adapters used, scores), per linear launch
+    n_used = len(set(int(k) for k in ids_np))
+    alg_bytes = (frames_np.size * 2 + 2.0 * (cfg.patch_dim * cfg.D + cfg.L * (4 * cfg.D * cfg.D + 2 * cfg.D * cfg.Dm))
+                 + n_used * 2.0 * cfg.L * cfg.r * (cfg.D + 3 * cfg.D + cfg.D + cfg.D) + R * cfg.C * 4) / n_gemm
+    traffic = measured_traffic_per_launch() if args.L0 == 0 else None
     roofline = {"bound": "mfma", "kernel": "bf16 MFMA linears: rowlayer_kernel (proj + LoRA + residual, LN, fc1, GELU, fc2, residual, LN, next qkv + LoRA in one launch per layer), rowlin_kernel (first qkv), gemm_bf16_dma_kernel (patch embedding)",
                 "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": LINEAR_HBM_BYTES_PER_LAUNCH if args.L0 == 0 else None,
+                "traffic": traffic, "traffic_source": os.path.relpath(TRAFFIC_PROFILE, ROOT) if traffic else None,
+                "algorithmic_bytes_per_launch": round(alg_bytes),
+                "traffic_over_algorithmic": round(traffic / alg_bytes, 1) if traffic else None,
                 "launches_per_step": n_gemm, "avg_launch_us": round(avg_ms * 1e3, 2),
                 "algorithmic_gflop_per_launch": round(flops / n_gemm / 1e9, 3)}
     stages = {k: {"launches_per_step": v["launches"] // n_prof, "us_per_step": round(v["ms"] * 1e3 / n_prof, 1)}
@@ -192,106 +458,17 @@ def main():
         step10, keep10 = make_step(cfg.polymorph_L0())
         sec10 = timed(step10, max(args.steps // 2, 10), 10)
         extra["frames_per_s_L0_10"] = round(F / sec10, 1)
+        if oracle is not None:
+            torch.cuda.synchronize()
+            want10 = oracle.forward(cfg, w, frames_np[:4], *synth.sets_to_csr([list(ids_np[off_np[f]:off_np[f + 1]]) for f in range(4)]), L0=10)
+            extra["max_abs_score_error_L0_10"] = float(np.abs(keep10[8].cpu().numpy()[:off_np[4]] - want10["scores"]).max())
         del step10, keep10
-        # isolated multi-LoRA linear (config 5): 256 x 197 x 768 -> 2304, 64 adapters r=16, 2 per block
-        case = synth.make_lora_linear_case()
-        elt = torch.bfloat16
-        up = lambda a, dt=elt: torch.from_numpy(np.ascontiguousarray(a)).to(device=dev, dtype=dt).contiguous()
-        X, Wt = up(case["X"]), up(case["W"].T)
-        At, Bt = up(np.swapaxes(case["A"], 1, 2)), up(np.swapaxes(case["B"], 1, 2))
-        bias = up(case["bias"], torch.float32)
-        o5, i5 = up(case["row_offsets"], torch.int32), up(case["adapter_ids"], torch.int32)
-        R5 = int(case["row_offsets"][-1])
-        Y = torch.empty(R5, 197, 2304, dtype=elt, device=dev)
-        ws5 = torch.empty(binding.poly_lora_linear_workspace_bytes(256, 197, 16, R5, 1), dtype=torch.uint8, device=dev)
-        run5 = lambda: binding.poly_lora_linear(X, Wt, bias, At, Bt, 1.0, o5, i5, R5, Y, ws5)
-        for _ in range(5):
-            run5()
-        torch.cuda.synchronize()
-        binding.poly_profile_begin(256)
-        for _ in range(20):
-            run5()
-        p5 = binding.poly_profile_end()
-        fl5 = 2.0 * 256 * 197 * 768 * 2304 + 2.0 * R5 * 197 * 16 * 2304        # base once per X block + expand
-        sh5 = 2.0 * R5 * 197 * 768 * 16
-        by5 = 2.0 * (256 * 197 * 768 + R5 * 197 * 2304 + 768 * 2304 + R5 * 197 * 16 + 64 * 16 * 2304)   # X, Y, W, S, Bt
-        g5 = p5["gemm"]["ms"] / p5["gemm"]["launches"] * 1e-3
-        s5 = p5["shrink"]["ms"] / p5["shrink"]["launches"] * 1e-3
-        extra["lora_linear_cfg5"] = {
-            "gemm_us": round(g5 * 1e6, 1), "gemm_tflops": round(fl5 / g5 / 1e12, 1), "gemm_frac_mfma": round(fl5 / g5 / 1e12 / PEAK_BF16_TFLOPS, 4),
-            "gemm_GBs": round(by5 / g5 / 1e9, 1), "gemm_frac_hbm": round(by5 / g5 / 1e9 / PEAK_HBM_GBS, 4),
-            "shrink_us": round(s5 * 1e6, 1),
-            "shrink_GBs": round(2 * (R5 * 197 * 768 + R5 * 197 * 16) / s5 / 1e9, 1),
-            "shrink_gflops": round(sh5 / s5 / 1e9, 1)}
-        del X, Wt, At, Bt, Y, ws5
-        # config 4: a 1024-frame label stream in 16 batches of 64 frames, poly_select + poly_forward per batch on the DeiT-tiny
-        # model (every batch reuses the same 64 synthetic frames: the cost of a batch depends on its adapter sets, not its pixels)
-        scores4_np, _ = synth.make_label_stream(1024)
-        model4 = binding.DeviceModel(cfg, w, L0=0)
-        frames4 = model4.frames_to_device(synth.make_frames(cfg, 64, np.random.default_rng(synth.seed_of(4))))
-        scores4 = torch.from_numpy(scores4_np).to(dev)
-        mem4 = torch.from_numpy(mem_np).to(dev)
-        cap4 = 3 * 64
-        off4 = torch.zeros(65, dtype=torch.int32, device=dev)
-        ids4 = torch.zeros(cap4, dtype=torch.int32, device=dev)
-        cnt4 = torch.zeros(2, dtype=torch.int32, device=dev)
-        out4 = torch.zeros(cap4, cfg.C, device=dev)
-        merged4 = torch.zeros(64, K_labels, device=dev)
-        ws4 = torch.empty(binding.poly_forward_workspace_bytes(model4, 64, cap4), dtype=torch.uint8, device=dev)
-
-        def stream_pass():
-            for a0 in range(0, 1024, 64):
-                binding.poly_select(scores4[a0:a0 + 64], mem4, off4, ids4, cnt4)
-                binding.poly_forward(model4, frames4, off4, ids4, cap4, out4, ws4, out_merged=merged4)
-        sec4 = timed(stream_pass, 5, 2)
-        binding.poly_select(scores4[960:1024], mem4, off4, ids4, cnt4)
-        torch.cuda.synchronize()
-        extra["stream_cfg4"] = {"frames_per_s": round(1024 / sec4, 1), "ms_per_64_frame_batch": round(sec4 / 16 * 1e3, 3),
-                                "row_blocks_last_batch": int(cnt4.cpu().numpy()[0])}
-        del model4, ws4
-        # the lagged loop (Fig. 3b): the same model with the paper's placement (adapters on the last 20 % of the layers), a base
-        # head over the 80 labels on the shared layers' output, Alg. 2 on the previous frame's scores and the adapted layers, one
-        # call per 64 frames of the stream; nothing comes back to the host between the steps
-        model6 = binding.DeviceModel(cfg, w, L0=10)
-        bw6, bb6 = synth.make_base_head(cfg, K_labels, 78, bias_mean=-5.0)
-        s6 = binding.DeviceStream(model6, bw6, bb6, mem_np)
-        cap6 = 4 * 64
-        off6 = torch.zeros(65, dtype=torch.int32, device=dev)
-        ids6 = torch.zeros(cap6, dtype=torch.int32, device=dev)
-        cnt6 = torch.zeros(2, dtype=torch.int32, device=dev)
-        out6 = torch.zeros(cap6, cfg.C, device=dev)
-        base6 = torch.zeros(64, K_labels, device=dev)
-        merged6 = torch.zeros(64, K_labels, device=dev)
-        ws6 = torch.empty(binding.poly_stream_step_workspace_bytes(model6, 64, cap6, K_labels), dtype=torch.uint8, device=dev)
-
-        def loop_pass():
-            for _ in range(16):
-                binding.poly_stream_step(model6, s6, frames4, cap6, off6, ids6, cnt6, out6, ws6, out_base_scores=base6, out_merged=merged6)
-        sec6 = timed(loop_pass, 5, 2)
-        extra["lagged_loop_L0_10"] = {"frames_per_s": round(1024 / sec6, 1), "ms_per_64_frame_call": round(sec6 / 16 * 1e3, 3),
-                                      "row_blocks_last_call": int(cnt6.cpu().numpy()[0])}
-        del model6, frames4, ws6
-        # config 3: ViT-base, 64 frames, adapters on qkv, proj, fc1 and fc2 (forward alone; its adapter sets are given)
-        cfg3, w3, frames3_np, off3_np, ids3_np = synth.make_forward_case(3)
-        model3 = binding.DeviceModel(cfg3, w3, L0=0)
-        del w3
-        frames3 = model3.frames_to_device(frames3_np)
-        F3, R3 = frames3_np.shape[0], int(off3_np[-1])
-        off3 = torch.from_numpy(off3_np.astype(np.int32)).to(dev)
-        ids3 = torch.from_numpy(ids3_np.astype(np.int32)).to(dev)
-        out3 = torch.zeros(R3, cfg3.C, device=dev)
-        ws3 = torch.empty(binding.poly_forward_workspace_bytes(model3, F3, R3), dtype=torch.uint8, device=dev)
-        sec3 = timed(lambda: binding.poly_forward(model3, frames3, off3, ids3, R3, out3, ws3), 10, 3)
-        T3 = 1 + (cfg3.H // cfg3.patch) * (cfg3.W // cfg3.patch)
-        fl3 = R3 * cfg3.L * (2.0 * T3 * (4 * cfg3.D ** 2 + 2 * cfg3.D * cfg3.Dm) + 4.0 * T3 * T3 * cfg3.D
-                             + 2.0 * T3 * cfg3.r * (4 * cfg3.D + 2 * cfg3.D + 2 * (cfg3.D + cfg3.Dm))) + F3 * 2.0 * (T3 - 1) * 768 * cfg3.D
-        extra["vit_base_cfg3"] = {"frames_per_s": round(F3 / sec3, 1), "ms_per_call": round(sec3 * 1e3, 2), "row_blocks": R3,
-                                  "algorithmic_tflops": round(fl3 / sec3 / 1e12, 1), "frac_mfma": round(fl3 / sec3 / 1e12 / PEAK_BF16_TFLOPS, 4)}
-        del model3, frames3, ws3
+        for key in ("cfg5", "cfg4", "loop", "cfg3", "sweep", "tau", "sum", "preset"):
+            name, fn = side[key]
+            extra[name] = fn()
         result["extra"] = extra
 
-    if not args.no_cpu:
-        import oracle
+    if oracle is not None:
         threads = int(oracle.lib().omp_get_max_threads())
         t0 = time.perf_counter()
         o_off, o_ids, _ = oracle.select(scores_np, mem_np)
@@ -304,25 +481,6 @@ def main():
         result["max_abs_score_error_vs_oracle"] = err
 
     print(json.dumps(result))
-
-    if args.sweep:
-        # adapters per frame x placement (the synthetic analogue of the paper's Figs. 3-4): every frame gets exactly n adapters,
-        # ids uniform without replacement; the step is the same select + forward + merge as above
-        rng = np.random.default_rng(synth.seed_of(2) + 77)
-        table = {}
-        for n_ad in range(1, 6):
-            ids_s = np.concatenate([np.sort(rng.choice(cfg.n_adapters, size=n_ad, replace=False)) for _ in range(F)]).astype(np.int32)
-            off_s = (np.arange(F + 1) * n_ad).astype(np.int32)
-            sc_s = scores_for_sets(off_s, ids_s)
-            row = {}
-            for L0s in (0, cfg.polymorph_L0()):
-                step_s, keep_s = make_step(L0s, sc_s, 5)
-                sec_s = timed(step_s, 50, 10)
-                assert np.array_equal(keep_s[4].cpu().numpy(), off_s) and np.array_equal(keep_s[5].cpu().numpy()[:len(ids_s)], ids_s)
-                row[f"L0={L0s}"] = round(F / sec_s, 1)
-                del step_s, keep_s
-            table[str(n_ad)] = row
-        print(json.dumps({"sweep": "frames/s, config-2 model, 32 frames, n adapters on every frame", "adapters_per_frame": table}))
 
 
 if __name__ == "__main__":

@@ -242,7 +242,8 @@ __device__ __forceinline__ bool xcd_tile(int bid, int tiles_mtot, int tiles_n, i
 // BM x BN tile, WM x WN waves, each wave (BM/WM) x (BN/WN) = (MI*32) x (NJ*32); NS LDS stages of 64 k-columns.
 // EK, the epilogue: 0 = subtile by subtile (fp32 output with residual / position rows, or one column subtile per wave);
 // 1, 2 = row-wise for bf16 output (two column subtiles per wave): 2 when the host knows that a wave's region touches at most two
-// input blocks and every output block has one low-rank term of at most 16 ranks (all operands of a pass prefetched), 1 otherwise.
+// input blocks and every output block has one low-rank term of at most 16 ranks (all operands of a pass prefetched), 1 otherwise;
+// 3 = the same conditions and prefetching as 2 for fp32 output with a residual (no position rows), staged 32 rows at a time.
 template <int BM, int BN, int WM, int WN, int NS, int EK>
 __global__ __launch_bounds__(64 * WM * WN, (BM * BN >= 256 * 256 || NS * (BM + BN) * 128 > 80 * 1024) ? 1 : 2)
 void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
@@ -419,7 +420,7 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
         else wait_vm_and_barrier<0>();
         // every wave is past compute(it - 1): its stage can be refilled
         if (it >= 1 && it + NS - 1 < nk) issue(it + NS - 1, (it - 1) % NS);
-        if constexpr (EK == 2) {
+        if constexpr (EK >= 2) {
             if (it == it_ids) {                               // (younger than every tile load in flight: the counted waits over-wait at most)
                 fanout_arrived();
                 request_ids(0, kAv, kBv);
@@ -497,7 +498,7 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
             }
         };
 
-        if constexpr (EK == 2) {
+        if constexpr (EK >= 2) {
             // The host has checked: a region touches at most two input blocks, one low-rank term per output block, rank 8 or 16
             // in one 16-rank step.  All operands of a pass -- the Bt fragments of the two adapters, one S fragment per subtile and
             // one more for the subtile that straddles the block boundary -- are requested together, those of pass p + 1 before
@@ -529,32 +530,88 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
             };
             kA = __builtin_amdgcn_readfirstlane(kAv); kB = __builtin_amdgcn_readfirstlane(kBv);
             request_operands(0, kA, kB);
-            for (int p = 0; p < maxfan; ++p) {
+            // results of subtile i, column subtile j of the current pass: accumulators + the low-rank term(s)
+            auto result = [&](int i, int j, int tw) {
+                const bool inB = tw >= tB, both = !inB && tw + 32 > tB && tB < Rend && kB >= 0;
+                const bf16x8 f1 = (inB || lm < tB - tw) ? fs1[i] : zero8;   // rows of the other block add nothing
+                const bf16x8 f2 = lm >= tB - tw ? fs2 : zero8;
+                f32x16 cj = acc[i][j];
+                if (inB) {
+                    if (kB >= 0) cj = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwB[j], f1, cj, 0, 0, 0);
+                } else {
+                    if (kA >= 0) cj = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwA[j], f1, cj, 0, 0, 0);
+                    if (both) cj = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwB[j], f2, cj, 0, 0, 0);
+                }
+                return cj;
+            };
+            if constexpr (EK == 2) {
+                for (int p = 0; p < maxfan; ++p) {
 #pragma unroll
-                for (int i = 0; i < MI; ++i) {
-                    const int tw = R0 + 32 * i;
-                    if (tw >= Rend) break;
-                    const bool inB = tw >= tB, both = !inB && tw + 32 > tB && tB < Rend && kB >= 0;
-                    const bf16x8 f1 = (inB || lm < tB - tw) ? fs1[i] : zero8;   // rows of the other block add nothing
-                    const bf16x8 f2 = lm >= tB - tw ? fs2 : zero8;
+                    for (int i = 0; i < MI; ++i) {
+                        const int tw = R0 + 32 * i;
+                        if (tw >= Rend) break;
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j) {               // one column subtile at a time: 16 live result registers, not 32
-                        f32x16 cj = acc[i][j];
-                        if (inB) {
-                            if (kB >= 0) cj = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwB[j], f1, cj, 0, 0, 0);
-                        } else {
-                            if (kA >= 0) cj = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwA[j], f1, cj, 0, 0, 0);
-                            if (both) cj = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fwB[j], f2, cj, 0, 0, 0);
+                        for (int j = 0; j < NJ; ++j) stage1(result(i, j, tw), i, j);   // one column subtile at a time: 16 live result registers
+                    }
+                    kA = __builtin_amdgcn_readfirstlane(kAnv); kB = __builtin_amdgcn_readfirstlane(kBnv);
+                    if (p + 1 < maxfan) {
+                        request_operands(p + 1, kA, kB);
+                        request_ids(p + 2, kAnv, kBnv);
+                    }
+                    store_rows(p);
+                }
+            } else {
+                // fp32 output with a residual: 32 rows at a time through the wave's 8 KB of LDS (16-byte chunks swizzled by row & 15),
+                // whole 256-byte row segments out, 4 rows per store.  The residual rows of a subtile are requested before its MFMAs
+                // and without per-lane conditions (rows past the end read a clamped row and are dropped at the store).
+                float *stg32 = (float *)dsmem + wave * (32 * RCOLS);
+                const int rrow = lane >> 4, rch = lane & 15;
+                const int col4 = n0 + wn * RCOLS + rch * 4;
+                const bool col4_ok = col4 < g.N;
+                const int cfix = col4_ok ? col4 : g.N - 4;
+                for (int p = 0; p < maxfan; ++p) {
+                    const int obA = oA0 + p < oA1 ? oA0 + p : -1, obB = (hasB && oB0 + p < oB1) ? oB0 + p : -1;
+                    const int rbA = (g.res && obA >= 0) ? (g.res_block_of_out ? g.res_block_of_out[obA] : obA) : 0;
+                    const int rbB = (g.res && obB >= 0) ? (g.res_block_of_out ? g.res_block_of_out[obB] : obB) : 0;
+#pragma unroll
+                    for (int i = 0; i < MI; ++i) {
+                        const int tw = R0 + 32 * i;
+                        if (tw >= Rend) break;
+                        f32x4 rv[8];
+                        int obq[8];
+                        long oq[8];
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) {
+                            const int t = min(tw + 4 * q + rrow, Rend - 1);
+                            const bool inB = t >= tB;
+                            const int trow = t - (inB ? tB : baseA);
+                            obq[q] = (tw + 4 * q + rrow < Rend) ? (inB ? obB : obA) : -1;
+                            oq[q] = ((long)max(obq[q], 0) * g.Tout + g.t_off + trow) * g.N;
+                            const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
+                            rv[q] = g.res ? *(const f32x4 *)(g.res + ((long)(inB ? rbB : rbA) * g.Tout + g.t_off + trow) * g.N + cfix) : z4;
                         }
-                        stage1(cj, i, j);
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) {
+                            const f32x16 cj = result(i, j, tw);
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const f32x4 v = {cj[4 * q], cj[4 * q + 1], cj[4 * q + 2], cj[4 * q + 3]};
+                                *(f32x4 *)(stg32 + lm * RCOLS + (((j * 8 + 2 * q + lh) ^ (lm & 15)) << 2)) = v;
+                            }
+                        }
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) {
+                            const int row = 4 * q + rrow;
+                            const f32x4 v = *(const f32x4 *)(stg32 + row * RCOLS + ((rch ^ (row & 15)) << 2)) + rv[q];
+                            if (obq[q] >= 0 && col4_ok) *(f32x4 *)((float *)g.out + oq[q] + col4) = v;
+                        }
+                    }
+                    kA = __builtin_amdgcn_readfirstlane(kAnv); kB = __builtin_amdgcn_readfirstlane(kBnv);
+                    if (p + 1 < maxfan) {
+                        request_operands(p + 1, kA, kB);
+                        request_ids(p + 2, kAnv, kBnv);
                     }
                 }
-                kA = __builtin_amdgcn_readfirstlane(kAnv); kB = __builtin_amdgcn_readfirstlane(kBnv);
-                if (p + 1 < maxfan) {
-                    request_operands(p + 1, kA, kB);
-                    request_ids(p + 2, kAnv, kBnv);
-                }
-                store_rows(p);
             }
         } else {
             for (int p = 0; p < maxfan; ++p) {
@@ -868,13 +925,17 @@ template <int BM, int BN, int WM, int WN, int NS>
 static void launch_dma(const GemmArgs &g, hipStream_t st)
 {
     if constexpr (BN / WN == 64) {
+        // a wave's region of BM / WM rows touches at most two input blocks when a block is at least that long (or when tiles
+        // stay inside blocks: Tb == 0)
+        const bool two_blocks = g.Tb == 0 || g.Tb >= BM / WM;
+        const bool prefetchable = two_blocks && !g.set_off && (!g.S || (g.RP == 16 && g.r % 8 == 0));
         if (g.mode != EPI_RESID) {
-            // a wave's region of BM / WM rows touches at most two input blocks when a block is at least that long (or when tiles
-            // stay inside blocks: Tb == 0)
-            const bool two_blocks = g.Tb == 0 || g.Tb >= BM / WM;
-            if (two_blocks && !g.set_off && (!g.S || (g.RP == 16 && g.r % 8 == 0))) launch_dma_ek<BM, BN, WM, WN, NS, 2>(g, st);
+            if (prefetchable) launch_dma_ek<BM, BN, WM, WN, NS, 2>(g, st);
             else launch_dma_ek<BM, BN, WM, WN, NS, 1>(g, st);
             return;
+        }
+        if constexpr (BM / WM <= 64) {   // (with four row subtiles per wave the residual rows in flight do not fit beside the accumulators)
+            if (prefetchable && !g.pos) { launch_dma_ek<BM, BN, WM, WN, NS, 3>(g, st); return; }
         }
     }
     launch_dma_ek<BM, BN, WM, WN, NS, 0>(g, st);

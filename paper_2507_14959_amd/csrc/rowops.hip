@@ -2,6 +2,8 @@
 // LoRA shrink (x A_k), per-adapter heads with sigmoid, and the optional merge to label space.
 #include "poly_dev.h"
 
+#include <type_traits>
+
 namespace {
 
 // ------------------------------------------------------------------ CSR check + row maps
@@ -145,13 +147,21 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *x, T *y
 
 // ------------------------------------------------------------------ LoRA shrink
 // bf16: one workgroup per 32 rows of one output block; S = scale * X At_k^T on the MFMA, operands read straight
-// from global memory (each lane 16 contiguous bytes along K). The four waves take a quarter of K each, so a
-// short row still has many loads in flight; the partial sums meet in LDS and every wave finishes eight of the
-// rows. Result zero padded to RP columns.
+// from global memory (each lane 16 contiguous bytes along K). The four waves take a quarter of K each and the
+// partial sums meet in LDS, where every wave finishes eight of the rows. Result zero padded to RP columns.
+//
+// The kernel moves few bytes per workgroup, so its time is the length of its chain of dependent memory round trips,
+// not its instruction count: everything that needs only the block index is requested in one go (true count, input
+// block, adapter ids), then -- when output blocks are paired -- the fan-out offsets, then all operand loads of a
+// batch of SH_NB K-steps at once (X rows and At rows, clamped instead of predicated: rows past T and ranks past r
+// feed results that are dropped or zeroed at the store).  K = 768 is one batch per wave: three round trips in all.
+//
 // With ranks of at most 16 a 32 x 32 MFMA tile has room for two adapters: where consecutive output blocks read the
 // same input block (the fan-out of a frame into its row-blocks; pair_off = the CSR offsets of the input blocks) the
 // workgroup of the even one does both -- columns 0-15 adapter k(ob), 16-31 adapter k(ob + 1) -- and the input rows
 // are read once instead of twice.
+constexpr int SH_NB = 12;   // 16-element K steps whose operands are in flight together (8 registers each)
+
 __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *X, int T, int K, const bf16_t *At, int r, int RP,
                                                           float scale, int n_out, const int *n_out_dev,
                                                           const int *in_block_of_out, const int *adapter_of_out, const int *pair_off,
@@ -160,23 +170,28 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *X, int T
     __shared__ float red[4][16][64];
     const int subs = (T + 31) / 32;
     const int ob = blockIdx.x / subs, sub = blockIdx.x % subs;
-    const int n = n_out_dev ? min(*n_out_dev, n_out) : n_out;
-    if (ob >= n) return;
-    const int xb = in_block_of_out ? in_block_of_out[ob] : ob;
     const bool paired = pair_off && in_block_of_out && RP == 16;
+    // first round trip: four loads with unconditional addresses, so that they are requested together.  The arrays have
+    // n_out entries; those past the true count are read here but never used.
+    const int *pn = n_out_dev ? n_out_dev : adapter_of_out, *pi = in_block_of_out ? in_block_of_out + ob : adapter_of_out + ob;
+    // (volatile: the compiler would otherwise sink each load below the early exit that precedes its first use)
+    const int n_ld = *(const volatile int *)pn, xb_ld = *(const volatile int *)pi;
+    const int k1_raw = *(const volatile int *)(adapter_of_out + ob), k2_raw = *(const volatile int *)(adapter_of_out + min(ob + 1, n_out - 1));
+    const int n = n_out_dev ? min(n_ld, n_out) : n_out, xb = in_block_of_out ? xb_ld : ob;
+    if (ob >= n) return;
     int ob2 = -1;
-    if (paired) {
-        if ((ob - pair_off[xb]) & 1) return;                 // done by the workgroup of ob - 1
-        if (ob + 1 < min(pair_off[xb + 1], n)) ob2 = ob + 1;
+    if (paired) {                                                // second round trip
+        const int p0 = *(const volatile int *)(pair_off + xb), p1 = *(const volatile int *)(pair_off + xb + 1);
+        if ((ob - p0) & 1) return;                               // done by the workgroup of ob - 1
+        if (ob + 1 < min(p1, n)) ob2 = ob + 1;
     }
-    const int k_ad = adapter_of_out[ob], k_ad2 = ob2 >= 0 ? adapter_of_out[ob2] : -1;
+    const int k_ad = k1_raw, k_ad2 = ob2 >= 0 ? k2_raw : -1;
     if (k_ad < 0 && k_ad2 < 0) return;
-    const int q = threadIdx.x >> 6, lane = threadIdx.x & 63, lm = lane & 31, lh = lane >> 5;
-    const int t = sub * 32 + lm;
-    const bf16_t *xr = X + ((size_t)xb * T + min(t, T - 1)) * K + lh * 8;
+    const int q = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, lm = lane & 31, lh = lane >> 5;
+    const bf16_t *xr = X + ((size_t)xb * T + min(sub * 32 + lm, T - 1)) * K + lh * 8;
     const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    const int steps = (K + 15) / 16, per = (steps + 3) / 4;
-    const int s0 = q * per, s1 = min(steps, s0 + per);
+    const int steps = K >> 4, per = (steps + 3) / 4;             // full steps; a last half step (K % 16 == 8) goes to wave 3
+    const int s0 = min(q * per, steps), s1 = min(steps, s0 + per);
     for (int j0 = 0; j0 < (paired ? 32 : RP); j0 += 32) {
         // column j0 + lm of the MFMA tile: rank `rank` of adapter `ksel`, stored to output block `osel`
         const int j = j0 + lm;
@@ -187,24 +202,26 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *X, int T
         f32x16 acc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-        int st = s0;
-        for (; st + 4 <= s1; st += 4) {
-            bf16x8 fa[4], fb[4];
+        // NB steps from step st on: every load of the batch is requested before the first MFMA waits
+        auto batch = [&](auto nb, int st) {
+            constexpr int NB = decltype(nb)::value;
+            bf16x8 fa[NB], fb[NB];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int k = (st + u) * 16;
-                const bool kin = k + lh * 8 + 8 <= K;
-                fa[u] = (t < T && kin) ? *(const bf16x8 *)(xr + k) : zero8;
-                fb[u] = (col_live && kin) ? *(const bf16x8 *)(ar + k) : zero8;
+            for (int u = 0; u < NB; ++u) {
+                fa[u] = *(const bf16x8 *)(xr + (st + u) * 16);
+                fb[u] = *(const bf16x8 *)(ar + (st + u) * 16);
             }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u], fb[u], acc, 0, 0, 0);
-        }
-        for (; st < s1; ++st) {
-            const int k = st * 16;
-            const bool kin = k + lh * 8 + 8 <= K;
-            const bf16x8 fa = (t < T && kin) ? *(const bf16x8 *)(xr + k) : zero8;
-            const bf16x8 fb = (col_live && kin) ? *(const bf16x8 *)(ar + k) : zero8;
+            for (int u = 0; u < NB; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u], fb[u], acc, 0, 0, 0);
+        };
+        int st = s0;                                             // (the counts are the same for the whole wave: scalar branches)
+        for (; st + SH_NB <= s1; st += SH_NB) batch(std::integral_constant<int, SH_NB>(), st);
+        for (; st + 4 <= s1; st += 4) batch(std::integral_constant<int, 4>(), st);
+        for (; st < s1; ++st) batch(std::integral_constant<int, 1>(), st);
+        if ((K & 15) && q == 3) {                                // K % 16 == 8: the upper half of the last step is past the row
+            const bf16x8 fa = lh == 0 ? *(const bf16x8 *)(xr + steps * 16) : zero8;
+            const bf16x8 fb = lh == 0 ? *(const bf16x8 *)(ar + steps * 16) : zero8;
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
         }
         if (j0) __syncthreads();
@@ -217,7 +234,7 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *X, int T
                 const int e = 4 * q + i;
                 const float v = red[0][e][lane] + red[1][e][lane] + red[2][e][lane] + red[3][e][lane];
                 const int tt = sub * 32 + 8 * q + 4 * lh + i;
-                if (tt < T) S[((size_t)osel * T + tt) * RP + (paired ? rank : j)] = (bf16_t)(scale * v);
+                if (tt < T) S[((size_t)osel * T + tt) * RP + (paired ? rank : j)] = col_live ? (bf16_t)(scale * v) : (bf16_t)0.f;
             }
         }
     }

@@ -290,6 +290,14 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
         for (int i = 0; i < BG; ++i) POLY_GLDS16(Wt + gb[i] + kt * BK, st + A_EL + (wave * BG + i) * 512);
     };
 
+    auto issue_one = [&](int kt, int s, int l) {            // load l (of NLD) of this wave for k-tile kt into stage s
+        bf16_t *st = dsmem + s * STAGE_EL;
+#pragma unroll
+        for (int i = 0; i < AG; ++i) if (l == i) POLY_GLDS16(A + ga[i] + kt * BK, st + (wave * AG + i) * 512);
+#pragma unroll
+        for (int i = 0; i < BG; ++i) if (l == AG + i) POLY_GLDS16(Wt + gb[i] + kt * BK, st + A_EL + (wave * BG + i) * 512);
+    };
+
     // Row-wise epilogue (two column subtiles per wave, bf16 output): the accumulators start from the bias, so no output block
     // has to add it later.  These loads go out before the tile loads: the in-order load counter then never makes their first
     // use wait for a tile.
@@ -419,7 +427,8 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
         else if (ahead == 1) wait_vm_and_barrier<NLD>();
         else wait_vm_and_barrier<0>();
         // every wave is past compute(it - 1): its stage can be refilled
-        if (it >= 1 && it + NS - 1 < nk) issue(it + NS - 1, (it - 1) % NS);
+        const bool refill = it >= 1 && it + NS - 1 < nk;
+        const int rkt = it + NS - 1, rst = (it + NS - 1) % NS;
         if constexpr (EK >= 2) {
             if (it == it_ids) {                               // (younger than every tile load in flight: the counted waits over-wait at most)
                 fanout_arrived();
@@ -439,7 +448,23 @@ void gemm_bf16_dma_kernel(const GemmArgs g, int tiles_m, int tiles_n)
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < NJ; ++j) {
+                    // The refill of the stage that was read in the previous step, spread over this step: PER loads per 16
+                    // k-columns, one every GAP MFMAs.  Issued as one burst the loads hold the wave at the issue stage until the
+                    // L2 path has taken them, and the MFMAs behind them start that much later.
+                    constexpr int NM = MI * NJ, PER = (NLD + 3) / 4;
+                    constexpr int GAP = NM / PER > 0 ? NM / PER : 1;
+                    const int m = i * NJ + j;
+                    if (m % GAP == 0 && m / GAP < PER) {
+                        const int l = kk * PER + m / GAP;
+                        if (l < NLD) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (refill) issue_one(rkt, rst, l);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+                }
         }
     }
     __syncthreads();   // all loads have landed (vmcnt(0) above) and all waves are done with the tiles
@@ -951,7 +976,7 @@ static int launch_gemm_dma(const GemmArgs &g, hipStream_t st)
     if (big && g.N % 256 == 0 && tiles256 >= 512) {
         launch_dma<256, 256, 2, 4, 2>(g, st);
     } else if (big && g.N % 128 == 0 && (long)g.n_in * ((g.T + 255) / 256) * ((g.N + 127) / 128) >= 512) {
-        launch_dma<256, 128, 4, 2, 2>(g, st);
+        launch_dma<256, 128, 4, 2, 3>(g, st);
     } else if (g.N % 128 == 0 || g.N >= 1024) {
         launch_dma<128, 128, 2, 2, 2>(g, st);
     } else if ((long)g.n_in * ((g.T + 127) / 128) * ((g.N + 63) / 64) < 256) {

@@ -146,35 +146,41 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const float *x, T *y
 }
 
 // ------------------------------------------------------------------ LoRA shrink
-// bf16: one workgroup per 32 rows of one output block; S = scale * X At_k^T on the MFMA, operands read straight
-// from global memory (each lane 16 contiguous bytes along K). The four waves take a quarter of K each and the
-// partial sums meet in LDS, where every wave finishes eight of the rows. Result zero padded to RP columns.
+// bf16: S = scale * X At_k^T (zero padded to RP columns) with v_mfma_f32_16x16x32_bf16, operands read straight from
+// global memory: a lane's 16 bytes are 8 consecutive K elements of one row, four lanes cover 64 contiguous bytes.
 //
-// The kernel moves few bytes per workgroup, so its time is the length of its chain of dependent memory round trips,
-// not its instruction count: everything that needs only the block index is requested in one go (true count, input
-// block, adapter ids), then -- when output blocks are paired -- the fan-out offsets, then all operand loads of a
-// batch of SH_NB K-steps at once (X rows and At rows, clamped instead of predicated: rows past T and ranks past r
-// feed results that are dropped or zeroed at the store).  K = 768 is one batch per wave: three round trips in all.
-//
-// With ranks of at most 16 a 32 x 32 MFMA tile has room for two adapters: where consecutive output blocks read the
-// same input block (the fan-out of a frame into its row-blocks; pair_off = the CSR offsets of the input blocks) the
-// workgroup of the even one does both -- columns 0-15 adapter k(ob), 16-31 adapter k(ob + 1) -- and the input rows
-// are read once instead of twice.
-constexpr int SH_NB = 12;   // 16-element K steps whose operands are in flight together (8 registers each)
+// The kernel moves few bytes per workgroup, so its time is the length of a workgroup's chain of dependent memory
+// round trips and the number of workgroups in flight, not arithmetic.  Hence:
+//  - a workgroup covers only 16 * MS = 32 rows of one output block (many workgroups per CU; more rows per workgroup
+//    would re-read At_k less often but measured slower) and its four waves split K; the partial sums meet in LDS,
+//    where every wave finishes a quarter of the values;
+//  - everything that needs only the block index is requested in one go (true count, input block, adapter ids), then
+//    -- when output blocks are paired -- the fan-out offsets, then At_k and the rows of a whole batch of K steps at
+//    once; the rows of subtile m + 1 are requested before the MFMAs of subtile m.  Rows past T and ranks past r are
+//    clamped, not predicated: they feed results that are dropped or zeroed at the store.
+// A 16-column MFMA tile is one "group": NG = 2 groups are the two rank halves of an adapter of rank 17-32 or, with
+// ranks of at most 16, two adapters: where consecutive output blocks read the same input block (the fan-out of a
+// frame into its row-blocks; pair_off = the CSR offsets of the input blocks) the workgroup of the even one does
+// both and the input rows are read once instead of twice.
+constexpr int SH_NS = 6;    // 32-element K steps whose operands are in flight together
 
+template <int MS, int NG>
 __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *X, int T, int K, const bf16_t *At, int r, int RP,
                                                           float scale, int n_out, const int *n_out_dev,
                                                           const int *in_block_of_out, const int *adapter_of_out, const int *pair_off,
                                                           bf16_t *S)
 {
-    __shared__ float red[4][16][64];
-    const int subs = (T + 31) / 32;
-    const int ob = blockIdx.x / subs, sub = blockIdx.x % subs;
-    const bool paired = pair_off && in_block_of_out && RP == 16;
+    constexpr int NV = MS * NG * 4;                              // values per lane and wave
+    constexpr int RV = NV < 32 ? NV : 32;                        // values per reduction round
+    static_assert(RV % 4 == 0, "reduction rounds");
+    __shared__ float red[4][RV][64];
+    const int subs = (T + 16 * MS - 1) / (16 * MS);
+    const int ob = blockIdx.x / subs, row0 = (blockIdx.x % subs) * (16 * MS);
+    const bool paired = NG == 2 && pair_off && in_block_of_out && RP == 16;
     // first round trip: four loads with unconditional addresses, so that they are requested together.  The arrays have
     // n_out entries; those past the true count are read here but never used.
-    const int *pn = n_out_dev ? n_out_dev : adapter_of_out, *pi = in_block_of_out ? in_block_of_out + ob : adapter_of_out + ob;
     // (volatile: the compiler would otherwise sink each load below the early exit that precedes its first use)
+    const int *pn = n_out_dev ? n_out_dev : adapter_of_out, *pi = in_block_of_out ? in_block_of_out + ob : adapter_of_out + ob;
     const int n_ld = *(const volatile int *)pn, xb_ld = *(const volatile int *)pi;
     const int k1_raw = *(const volatile int *)(adapter_of_out + ob), k2_raw = *(const volatile int *)(adapter_of_out + min(ob + 1, n_out - 1));
     const int n = n_out_dev ? min(n_ld, n_out) : n_out, xb = in_block_of_out ? xb_ld : ob;
@@ -187,54 +193,93 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *X, int T
     }
     const int k_ad = k1_raw, k_ad2 = ob2 >= 0 ? k2_raw : -1;
     if (k_ad < 0 && k_ad2 < 0) return;
-    const int q = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, lm = lane & 31, lh = lane >> 5;
-    const bf16_t *xr = X + ((size_t)xb * T + min(sub * 32 + lm, T - 1)) * K + lh * 8;
-    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    const int steps = K >> 4, per = (steps + 3) / 4;             // full steps; a last half step (K % 16 == 8) goes to wave 3
-    const int s0 = min(q * per, steps), s1 = min(steps, s0 + per);
-    for (int j0 = 0; j0 < (paired ? 32 : RP); j0 += 32) {
-        // column j0 + lm of the MFMA tile: rank `rank` of adapter `ksel`, stored to output block `osel`
-        const int j = j0 + lm;
-        const bool second = paired && lm >= 16;
-        const int rank = paired ? (lm & 15) : j, ksel = second ? k_ad2 : k_ad, osel = second ? ob2 : ob;
-        const bool col_live = ksel >= 0 && rank < r;
-        const bf16_t *ar = At + ((size_t)max(ksel, 0) * r + min(rank, r - 1)) * K + lh * 8;
-        f32x16 acc;
+    const int q = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, li = lane & 15, lc = lane >> 4;
+    const bf16_t *xblk = X + (size_t)xb * T * K + lc * 8;
+    int xoff[MS];                                                // row li of subtile m (the host has checked T * K < 2^31)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-        // NB steps from step st on: every load of the batch is requested before the first MFMA waits
+    for (int m = 0; m < MS; ++m) xoff[m] = min(row0 + 16 * m + li, T - 1) * K;
+    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int steps = K >> 5, per = (steps + 3) / 4;             // full steps; what is left of K (8, 16 or 24) goes to wave 3
+    const int s0 = min(q * per, steps), s1 = min(steps, s0 + per);
+    for (int j0 = 0; j0 < (paired ? 16 : RP); j0 += 16 * NG) {
+        // group g, lane column li: rank `rank` of adapter `ksel`, stored to column `rank` of output block `osel`
+        int ksel[NG], osel[NG], rank[NG];
+        const bf16_t *ar[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const bool other = paired && g == 1;
+            ksel[g] = other ? k_ad2 : k_ad;
+            osel[g] = other ? ob2 : ob;
+            rank[g] = paired ? li : j0 + 16 * g + li;
+            ar[g] = At + ((size_t)max(ksel[g], 0) * r + min(rank[g], r - 1)) * K + lc * 8;
+        }
+        f32x4 acc[MS][NG];
+#pragma unroll
+        for (int m = 0; m < MS; ++m)
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[m][g] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // NB steps from step st on
         auto batch = [&](auto nb, int st) {
             constexpr int NB = decltype(nb)::value;
-            bf16x8 fa[NB], fb[NB];
+            bf16x8 fb[NG][NB], fa[2][NB];
 #pragma unroll
-            for (int u = 0; u < NB; ++u) {
-                fa[u] = *(const bf16x8 *)(xr + (st + u) * 16);
-                fb[u] = *(const bf16x8 *)(ar + (st + u) * 16);
+            for (int u = 0; u < NB; ++u)
+#pragma unroll
+                for (int g = 0; g < NG; ++g) fb[g][u] = *(const bf16x8 *)(ar[g] + (st + u) * 32);
+#pragma unroll
+            for (int u = 0; u < NB; ++u) fa[0][u] = *(const bf16x8 *)(xblk + xoff[0] + (st + u) * 32);
+#pragma unroll
+            for (int m = 0; m < MS; ++m) {
+                if (m + 1 < MS) {
+#pragma unroll
+                    for (int u = 0; u < NB; ++u) fa[(m + 1) & 1][u] = *(const bf16x8 *)(xblk + xoff[m + 1] + (st + u) * 32);
+                }
+                __builtin_amdgcn_sched_barrier(0);               // the next rows are requested before these MFMAs wait
+#pragma unroll
+                for (int u = 0; u < NB; ++u)
+#pragma unroll
+                    for (int g = 0; g < NG; ++g)
+                        acc[m][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[m & 1][u], fb[g][u], acc[m][g], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int u = 0; u < NB; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u], fb[u], acc, 0, 0, 0);
         };
         int st = s0;                                             // (the counts are the same for the whole wave: scalar branches)
-        for (; st + SH_NB <= s1; st += SH_NB) batch(std::integral_constant<int, SH_NB>(), st);
-        for (; st + 4 <= s1; st += 4) batch(std::integral_constant<int, 4>(), st);
+        for (; st + SH_NS <= s1; st += SH_NS) batch(std::integral_constant<int, SH_NS>(), st);
+        for (; st + 2 <= s1; st += 2) batch(std::integral_constant<int, 2>(), st);
         for (; st < s1; ++st) batch(std::integral_constant<int, 1>(), st);
-        if ((K & 15) && q == 3) {                                // K % 16 == 8: the upper half of the last step is past the row
-            const bf16x8 fa = lh == 0 ? *(const bf16x8 *)(xr + steps * 16) : zero8;
-            const bf16x8 fb = lh == 0 ? *(const bf16x8 *)(ar + steps * 16) : zero8;
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
+        if ((K & 31) && q == 3) {                                // the rest of K: chunks past the end of the row are zero
+            const bool in = steps * 32 + lc * 8 + 8 <= K;
+            bf16x8 fb[NG];
+#pragma unroll
+            for (int g = 0; g < NG; ++g) fb[g] = in ? *(const bf16x8 *)(ar[g] + steps * 32) : zero8;
+#pragma unroll
+            for (int m = 0; m < MS; ++m) {
+                const bf16x8 fa = in ? *(const bf16x8 *)(xblk + xoff[m] + steps * 32) : zero8;
+#pragma unroll
+                for (int g = 0; g < NG; ++g) acc[m][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb[g], acc[m][g], 0, 0, 0);
+            }
         }
-        if (j0) __syncthreads();
+        // value v = (m * NG + g) * 4 + e of a lane: row row0 + 16 m + 4 lc + e, column li of group g.  RV values per round;
+        // wave q finishes values [q RV / 4, (q + 1) RV / 4) of the round.
 #pragma unroll
-        for (int e = 0; e < 16; ++e) red[q][e][lane] = acc[e];
-        __syncthreads();
-        if (paired ? (ksel >= 0) : (j < RP && k_ad >= 0)) {
+        for (int v0 = 0; v0 < NV; v0 += RV) {
+            if (v0 || j0) __syncthreads();
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int e = 4 * q + i;
-                const float v = red[0][e][lane] + red[1][e][lane] + red[2][e][lane] + red[3][e][lane];
-                const int tt = sub * 32 + 8 * q + 4 * lh + i;
-                if (tt < T) S[((size_t)osel * T + tt) * RP + (paired ? rank : j)] = col_live ? (bf16_t)(scale * v) : (bf16_t)0.f;
+            for (int v = 0; v < RV; ++v)
+                if (v0 + v < NV) red[q][v][lane] = acc[(v0 + v) / (NG * 4)][((v0 + v) / 4) % NG][(v0 + v) & 3];
+            __syncthreads();
+#pragma unroll
+            for (int w = 0; w < RV / 4; ++w) {
+                const int vr = q * (RV / 4) + w, v = v0 + vr;    // (q is scalar: the three selections below are uniform)
+                const int m = v / (NG * 4), g = (v / 4) % NG, e = v & 3;
+                const float sum = red[0][vr][lane] + red[1][vr][lane] + red[2][vr][lane] + red[3][vr][lane];
+                const int tt = row0 + 16 * m + 4 * lc + e;
+                int ks = ksel[0], os = osel[0], rk = rank[0];
+#pragma unroll
+                for (int gg = 1; gg < NG; ++gg)
+                    if (g == gg) { ks = ksel[gg]; os = osel[gg]; rk = rank[gg]; }
+                if (v < NV && tt < T && ks >= 0 && os >= 0 && rk < RP)
+                    S[((size_t)os * T + tt) * RP + rk] = rk < r ? (bf16_t)(scale * sum) : (bf16_t)0.f;
             }
         }
     }
@@ -400,16 +445,28 @@ int launch_layernorm(const float *x, void *y, const float *gain, const float *sh
     return hip_ok();
 }
 
+template <int MS, int NG>
+static void launch_shrink_bf16(hipStream_t st, const bf16_t *X, int T, int K, const bf16_t *At, int r, int RP, float scale, int n_out,
+                               const int *n_out_dev, const int *in_block_of_out, const int *adapter_of_out, const int *pair_off, bf16_t *S)
+{
+    const int subs = (T + 16 * MS - 1) / (16 * MS);
+    POLY_LAUNCH(POLY_STAGE_SHRINK, (shrink_bf16_kernel<MS, NG>), dim3((unsigned)((size_t)n_out * subs)), dim3(256), st, X, T, K, At, r, RP, scale,
+                n_out, n_out_dev, in_block_of_out, adapter_of_out, pair_off, S);
+}
+
 int launch_shrink(const void *X, int T, int K, const void *At, int r, int RP, float scale, int n_out, const int *n_out_dev,
                   const int *in_block_of_out, const int *adapter_of_out, const int *pair_off, void *S, int dtype, hipStream_t st)
 {
     if (n_out == 0) return POLY_OK;
     if (dtype == POLY_BF16) {
-        if (K % 8 != 0) return POLY_EINVAL;
-        const int subs = (T + 31) / 32;
-        const unsigned blocks = (unsigned)((size_t)n_out * subs);
-        POLY_LAUNCH(POLY_STAGE_SHRINK, shrink_bf16_kernel, dim3(blocks), dim3(256), st, (const bf16_t *)X, T, K, (const bf16_t *)At, r, RP, scale, n_out,
-                           n_out_dev, in_block_of_out, adapter_of_out, pair_off, (bf16_t *)S);
+        if (K % 8 != 0 || (long)T * K > 0x7fffffffL) return POLY_EINVAL;
+        const bool two_groups = RP > 16 || (pair_off && in_block_of_out);
+        if (two_groups)
+            launch_shrink_bf16<2, 2>(st, (const bf16_t *)X, T, K, (const bf16_t *)At, r, RP, scale, n_out, n_out_dev, in_block_of_out,
+                                     adapter_of_out, pair_off, (bf16_t *)S);
+        else
+            launch_shrink_bf16<2, 1>(st, (const bf16_t *)X, T, K, (const bf16_t *)At, r, RP, scale, n_out, n_out_dev, in_block_of_out,
+                                     adapter_of_out, pair_off, (bf16_t *)S);
     } else {
         const size_t total = (size_t)n_out * T * RP;
         const unsigned blocks = (unsigned)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);

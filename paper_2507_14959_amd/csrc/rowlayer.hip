@@ -564,7 +564,21 @@ __global__ __launch_bounds__(LY_THREADS) void rowlayer_kernel(const RowLayerArgs
     const int i0q = NA + nch;                    // first item of C
     if (loader) {
         for (int s = 0; 2 * s < nchq; ++s) {
-            wait_item(i0q + min(2 * s + 1, nchq - 1));
+            if (s == 0 && wave == 4) {
+                // The first two chunks of C were requested by this wave before it stored its rows of x''; chunks 2-4 are wave 0's
+                // (`last` counts them, so wait_item would let two items' worth of this wave's requests stay in flight and
+                // guarantee nothing about chunk 1).  What may stay in flight is exactly the stores: KT per group of 16 rows
+                // that has a row of this wave's inside the tile -- the stores that are issued whatever the compiler does with
+                // the others.
+                switch (min(4, (rows + 15) >> 4)) {
+                case 4: rl_wait_barrier<4 * KT>(); break;
+                case 3: rl_wait_barrier<3 * KT>(); break;
+                case 2: rl_wait_barrier<2 * KT>(); break;
+                default: rl_wait_barrier<KT>(); break;
+                }
+            } else {
+                wait_item(i0q + min(2 * s + 1, nchq - 1));
+            }
             if (s == 0 && lora_q) issue_bt(a.Bqt + (size_t)k_ad * Nq * a.r, Nq, a.r);   // the computing waves hold their fragments by now
             refill(PC + 2 * s - 1, 1 << 30);
         }

@@ -37,6 +37,19 @@ def measured_traffic_per_launch():
     return None
 
 
+def measured_cfg3_traffic():
+    """HBM bytes per launch of the LayerNorm and the shrink kernel of config 3 from the tracked rocprofv3 counter summary (None without it)."""
+    out = {}
+    try:
+        for line in open(os.path.join(ROOT, "profiles", "bench_cfg3_vit_base_hbm_traffic.md")):
+            for key in ("layernorm_hbm_bytes_per_launch", "shrink_hbm_bytes_per_launch"):
+                if line.startswith(key + ":"):
+                    out[key] = float(line.split(":")[1].split()[0])
+    except OSError:
+        pass
+    return out
+
+
 def scores_for_sets(off, ids, n_groups=16, group_size=5):
     """Label scores whose active labels make Alg. 2 select exactly the given adapter sets."""
     F = len(off) - 1
@@ -229,6 +242,14 @@ def main():
                "layernorm_frac_hbm": round(ln_bytes / ln_us / 1e3 / PEAK_HBM_GBS, 4),
                "shrink_us_per_launch": round(sh_us, 1), "shrink_GBs": round(sh_bytes / sh_us / 1e3, 1),
                "shrink_frac_hbm": round(sh_bytes / sh_us / 1e3 / PEAK_HBM_GBS, 4)}
+        # the same two kernels against the bytes that the FETCH_SIZE / WRITE_SIZE counters saw (tracked profile; the live time is this run's)
+        m3 = measured_cfg3_traffic()
+        if "layernorm_hbm_bytes_per_launch" in m3:
+            res["layernorm_counter_bytes_per_launch"] = m3["layernorm_hbm_bytes_per_launch"]
+            res["layernorm_frac_hbm_counter_bytes"] = round(m3["layernorm_hbm_bytes_per_launch"] / ln_us / 1e3 / PEAK_HBM_GBS, 4)
+        if "shrink_hbm_bytes_per_launch" in m3:
+            res["shrink_counter_bytes_per_launch"] = m3["shrink_hbm_bytes_per_launch"]
+            res["shrink_frac_hbm_counter_bytes"] = round(m3["shrink_hbm_bytes_per_launch"] / sh_us / 1e3 / PEAK_HBM_GBS, 4)
         if oracle is not None:
             torch.cuda.synchronize()
             fs = (0, 37)
